@@ -1,0 +1,216 @@
+/*
+ * eep.h -- C ABI of the membership-elastic MoE dispatch/combine library for
+ * AMD MI355X (gfx950).
+ *
+ * The library implements, on ONE GPU, the per-step token dispatch and combine
+ * of a wide expert-parallel (EP) MoE layer whose membership is explicit,
+ * mutable device state (paper: Sec. 3.2 "Live EP Validity", Sec. 3.4 and
+ * Sec. 4.1 "GPU-Resident Peer Table", Fig. 4, Fig. 5, Fig. 7, Sec. 5.1
+ * "Expert-Location Metadata").  The R "virtual" EP ranks are partitions of one
+ * GPU's HBM: rank r owns the physical expert slots p = r*S .. r*S+S-1 and the
+ * rows of the receive buffer that those slots receive.
+ *
+ * Conventions
+ *   - Every entry point returns an int: 0 (EEP_OK) or a negative eep_status.
+ *     No C++ exception crosses this boundary.
+ *   - "host" pointers are ordinary process memory, read before the call
+ *     returns.  "device" pointers are HIP device memory of the GPU that was
+ *     current when eep_create ran; the caller owns them and keeps them alive
+ *     until the work queued on the stream has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All work is queued on it and no entry point synchronises, except where
+ *     stated (eep_create, eep_destroy, eep_read_view, eep_graph_*).
+ *   - The context owns the membership/placement tables and the layout arrays.
+ *     Their device addresses never change during the context's lifetime:
+ *     table updates rewrite contents only (Fig. 4, Fig. 8), which is what lets
+ *     a captured hipGraph keep replaying across failure and rejoin.
+ *   - Layouts are dense row-major; indices are int32.
+ *
+ * Notation: T tokens, k = top-k, H hidden elements, E logical experts,
+ * R ranks, S slots per rank (S_prim primary + S_red redundant), P = R*S
+ * physical slots, N = number of routed (token, k) pairs of the current step.
+ */
+#ifndef EEP_H_
+#define EEP_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EEP_OK = 0,
+  EEP_ERR_INVALID_ARG = -1, /* null pointer, size out of range, T % R != 0, bad enum */
+  EEP_ERR_ALIGN = -2,       /* a row size or a base pointer is not 16-byte aligned   */
+  EEP_ERR_COVERAGE = -3,    /* update would leave a logical expert with no live replica */
+  EEP_ERR_HIP = -4,         /* a HIP runtime call failed; see eep_last_hip_error     */
+  EEP_ERR_STATE = -5        /* call order violated (e.g. dispatch before dispatch_layout) */
+} eep_status;
+
+typedef enum { EEP_F32 = 0, EEP_BF16 = 1, EEP_FP8_E4M3 = 2 } eep_dtype;
+
+/* Which live replica serves a (token, expert) pair when several are live.
+ * The paper shows a single route per expert (Fig. 4, Fig. 5) and says the
+ * metadata records every location (Sec. 5.1) but gives no selection rule:
+ *   EEP_FIRST_LIVE  first live replica in canonical order (reproduces Fig. 5);
+ *   EEP_SPREAD      replica number (t mod n_live) for token t (balances load).
+ * Canonical order of the replicas of one expert: primary slots before
+ * redundant slots, then ascending slot id. */
+typedef enum { EEP_SPREAD = 0, EEP_FIRST_LIVE = 1 } eep_policy;
+
+typedef enum {
+  EEP_STUB_IDENTITY = 0, /* y[row] = recv_x[row]                       (same dtype) */
+  EEP_STUB_SCALE = 1,    /* y[row] = round(s[logical expert of row] * recv_x[row])  */
+  EEP_STUB_DEQUANT = 2   /* y[row] = bf16(e4m3(recv_x[row]) * recv_scale[row, h/G]) */
+} eep_stub_kind;
+
+typedef struct {
+  int32_t num_ranks;       /* R  >= 1                                              */
+  int32_t slots_per_rank;  /* S  >= 1                                              */
+  int32_t primary_slots;   /* S_prim in [0, S]; slots s >= S_prim are redundant    */
+  int32_t num_logical;     /* E  >= 1                                              */
+  int32_t max_tokens;      /* T_max >= 0, the largest T any per-step call may pass */
+  int32_t topk;            /* k in [1, 32]                                         */
+  int32_t hidden;          /* H  >= 1 elements per token row                       */
+  int32_t x_dtype;         /* eep_dtype of dispatch payload rows                   */
+  int32_t y_dtype;         /* eep_dtype of expert output rows (F32 or BF16)        */
+  int32_t out_dtype;       /* eep_dtype of combined rows      (F32 or BF16)        */
+  int32_t scale_group;     /* channels per fp32 scale (H % group == 0) when x_dtype
+                              is FP8_E4M3, else 0                                  */
+  int32_t policy;          /* eep_policy                                           */
+  int32_t strict_coverage; /* 1: a table update that would leave a logical expert
+                              without a live replica (validity condition 2,
+                              Sec. 3.2) returns EEP_ERR_COVERAGE and changes
+                              nothing; 0: it is applied and such pairs are dropped
+                              and counted in status[1]                             */
+} eep_config;
+
+typedef struct eep_ctx eep_ctx;
+
+/* Allocates the device tables and layout arrays on the current device
+ * (hipMalloc; sizes depend only on the config) and initialises them to
+ * "all ranks live, all slots empty".  Synchronises the device once.
+ * Row sizes (H * sizeof(dtype)) must be multiples of 16 bytes (EEP_ERR_ALIGN).
+ * On error *out is NULL. */
+int eep_create(const eep_config* cfg, eep_ctx** out);
+
+/* Waits for the device, frees everything the context owns.  NULL is OK. */
+int eep_destroy(eep_ctx* ctx);
+
+/* ---- table updates: between steps, stream-ordered (Sec. 3.1: repair and
+ * reintegration happen between forward passes; Sec. 4.1 "In-place peer-table
+ * updates"; Fig. 4) -------------------------------------------------------
+ * Both calls only queue small kernels that overwrite table CONTENTS at their
+ * fixed addresses; they do not allocate, synchronise or move any buffer, and
+ * they copy the host array before returning.  A step queued later on the same
+ * stream sees the new tables, one queued earlier sees the old ones.  Both may
+ * be called while a captured graph of the per-step calls exists; the graph
+ * needs no update afterwards.
+ *
+ * To stay valid at every step boundary follow the paper's order (Fig. 6):
+ *   failure: eep_update_placement(repaired), then eep_set_membership(dead);
+ *   rejoin:  eep_set_membership(live), then eep_update_placement(preferred). */
+
+/* active_host: host int32[R]; 0 = failed (receives nothing), non-zero = live.
+ * This is the `active` column of the peer table (Fig. 7). */
+int eep_set_membership(eep_ctx* ctx, const int32_t* active_host, void* stream);
+
+/* phys_to_logical_host: host int32[P]; entry p is the logical expert held by
+ * physical slot p = r*S + s, or -1 for an empty slot (Sec. 5.1).  Entries
+ * outside [-1, E) give EEP_ERR_INVALID_ARG. */
+int eep_update_placement(eep_ctx* ctx, const int32_t* phys_to_logical_host, void* stream);
+
+/* ---- per-step calls: graph-capturable, grids depend only on T ----------- */
+
+/* Routing + layout of one step.  topk_idx: device int32[T, k], the router's
+ * logical expert per (token, j).  T must satisfy 0 <= T <= T_max, T % R == 0
+ * (tokens [b*T/R, (b+1)*T/R) belong to source rank b).
+ * For every pair it picks the live replica slot (slot_of, or -1 when the
+ * index is outside [0, E), repeats an earlier index of the same token, or the
+ * expert has no live replica), counts pairs per slot, prefix-sums the counts
+ * into receive-buffer offsets, and gives every routed pair its row:
+ * rows of one slot are contiguous and ordered by ascending token.
+ * Results stay in the context (see eep_view). */
+int eep_dispatch_layout(eep_ctx* ctx, const int32_t* topk_idx, int32_t T, void* stream);
+
+/* recv_x[row_of[t, j], :] = x[t, :] for every routed pair (Fig. 7, dispatch
+ * path; inactive ranks are never written).  x: device [T, H] x_dtype;
+ * recv_x: device [T*k, H] x_dtype; rows >= N are left untouched.  With fp8
+ * payloads x_scale is device float[T, H/group] and recv_scale device
+ * float[T*k, H/group], moved the same way; otherwise both are NULL.
+ * Needs eep_dispatch_layout with the same T queued before it. */
+int eep_dispatch(eep_ctx* ctx, const void* x, const float* x_scale, void* recv_x,
+                 float* recv_scale, int32_t T, void* stream);
+
+/* out[t, :] = round( sum over routed j, ascending, of w[t, j] * y[row_of[t, j], :] ),
+ * accumulated in fp32 with one fused multiply-add per term, starting from 0
+ * (Sec. 4.1: combine reduces the expert outputs).  y: device [T*k, H] y_dtype;
+ * topk_w: device float[T, k]; out: device [T, H] out_dtype (bf16: round to
+ * nearest even).  A token with no routed pair gets zeros. */
+int eep_combine(eep_ctx* ctx, const void* y, const float* topk_w, void* out, int32_t T,
+                void* stream);
+
+/* Stand-in for the expert kernels that sit between dispatch and combine in the
+ * captured graph (Fig. 4).  Processes rows [0, N) only; the grid is sized for
+ * T*k rows and reads N from device memory.
+ *   IDENTITY: copies recv_x to y (callers may instead alias y = recv_x);
+ *   SCALE:    expert_scale is device float[E]; x_dtype must equal y_dtype
+ *             (F32 or BF16); product computed in fp32;
+ *   DEQUANT:  x_dtype FP8_E4M3 (OCP e4m3fn), y_dtype BF16. */
+int eep_expert_stub(eep_ctx* ctx, int32_t kind, const void* recv_x, const float* recv_scale,
+                    const float* expert_scale, void* y, int32_t T, void* stream);
+
+/* ---- introspection ------------------------------------------------------ */
+
+/* Device addresses of the context's arrays (all int32, stable for the
+ * context's lifetime; contents valid once the producing call has finished on
+ * its stream).
+ *   active[R], phys_to_logical[P], l2p_off[E+1], l2p_list[P]  tables
+ *   slot_of[T,k], row_of[T,k]      per pair; -1 when not routed
+ *   src_of[T*k]                    row -> t*k+j; -1 for rows >= N
+ *   count[P], offset[P+1]          pairs per slot, exclusive prefix sum
+ *   rank_count[R], rank_offset[R+1]
+ *   cnt_src[R,P]                   pairs per (source rank, slot)
+ *   status[4]                      {N, n_uncovered, n_masked, table version} */
+typedef struct {
+  const int32_t *active, *phys_to_logical, *l2p_off, *l2p_list;
+  const int32_t *slot_of, *row_of, *src_of;
+  const int32_t *count, *offset, *rank_count, *rank_offset, *cnt_src, *status;
+} eep_view;
+int eep_get_view(eep_ctx* ctx, eep_view* out);
+
+typedef enum {
+  EEP_V_ACTIVE = 0, EEP_V_PHYS_TO_LOGICAL, EEP_V_L2P_OFF, EEP_V_L2P_LIST, EEP_V_SLOT_OF,
+  EEP_V_ROW_OF, EEP_V_SRC_OF, EEP_V_COUNT, EEP_V_OFFSET, EEP_V_RANK_COUNT,
+  EEP_V_RANK_OFFSET, EEP_V_CNT_SRC, EEP_V_STATUS, EEP_V_NUM_FIELDS
+} eep_view_field;
+
+/* Debug helper: waits for `stream`, then copies the first n int32 of one view
+ * array into host memory.  n beyond the array's allocated size is an error. */
+int eep_read_view(eep_ctx* ctx, int32_t field, int32_t* host_dst, int64_t n, void* stream);
+
+const char* eep_strerror(int code);
+/* hipError_t of the last failed HIP call made for this context (0 if none). */
+int eep_last_hip_error(eep_ctx* ctx);
+
+/* ---- hipGraph helper (Sec. 2.3, Fig. 4: capture once, replay, patch table
+ * contents only) ------------------------------------------------------------
+ * eep_graph_begin puts `stream` (not the default stream) into capture mode;
+ * the per-step calls made on it until eep_graph_end are recorded, not run.
+ * eep_graph_end instantiates the graph exactly once.  eep_graph_launch replays
+ * it on `stream`.  The library never calls hipGraphExecUpdate and never
+ * re-instantiates; eep_graph_counters reports how often each happened so that
+ * a test can assert it. */
+typedef struct eep_graph eep_graph;
+int eep_graph_begin(eep_ctx* ctx, void* stream);
+int eep_graph_end(eep_ctx* ctx, void* stream, eep_graph** out);
+int eep_graph_launch(eep_graph* g, void* stream);
+int eep_graph_destroy(eep_graph* g);
+/* counters[0] = instantiations, [1] = exec updates, [2] = launches of this graph. */
+int eep_graph_counters(const eep_graph* g, int64_t counters[3]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EEP_H_ */

@@ -1,0 +1,166 @@
+"""Python face of the C oracle (oracle/eep_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the CPU-baseline leg of
+the benchmark may import this; the product package never does.  This file only
+marshals numpy arrays into the C functions; all arithmetic lives in the C file.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SPREAD, FIRST_LIVE = 0, 1
+F32, BF16 = 0, 1
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(_build.build(force=False))
+        _lib.eeo_tables.restype = ctypes.c_int
+        _lib.eeo_uncovered_experts.restype = ctypes.c_int
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def tables(p2l, E, S, S_prim):
+    """O1 -> (l2p_off[E+1], l2p_list[P])."""
+    p2l = _i32(p2l)
+    P = p2l.size
+    off = np.empty(E + 1, np.int32)
+    lst = np.empty(P, np.int32)
+    rc = lib().eeo_tables(P, E, S, S_prim, _p(p2l), _p(off), _p(lst))
+    if rc != 0:
+        raise ValueError("phys_to_logical entry outside [-1, E)")
+    return off, lst
+
+
+def uncovered_experts(p2l, active, E, S):
+    p2l, active = _i32(p2l), _i32(active)
+    return lib().eeo_uncovered_experts(p2l.size, E, S, _p(p2l), _p(active))
+
+
+def map_pairs(topk_idx, l2p_off, l2p_list, active, E, S, policy):
+    """O2 -> (slot_of[T,k], n_uncovered, n_masked)."""
+    topk_idx = _i32(topk_idx)
+    T, k = topk_idx.shape
+    slot_of = np.empty((T, k), np.int32)
+    counters = np.zeros(2, np.int64)
+    lib().eeo_map(T, k, E, S, policy, _p(topk_idx), _p(_i32(l2p_off)), _p(_i32(l2p_list)),
+                  _p(_i32(active)), _p(slot_of), _p(counters))
+    return slot_of, int(counters[0]), int(counters[1])
+
+
+def layout(slot_of, R, S):
+    """O3-O5 -> dict(count, rank_count, cnt_src, offset, rank_offset, row_of, src_of)."""
+    slot_of = _i32(slot_of)
+    T, k = slot_of.shape
+    if T % R != 0:
+        raise ValueError("T must be a multiple of R")
+    P = R * S
+    out = dict(count=np.empty(P, np.int32), rank_count=np.empty(R, np.int32),
+               cnt_src=np.empty((R, P), np.int32), offset=np.empty(P + 1, np.int32),
+               rank_offset=np.empty(R + 1, np.int32), row_of=np.empty((T, k), np.int32),
+               src_of=np.empty(T * k, np.int32))
+    cursor = np.empty(P, np.int32)
+    lib().eeo_layout(T, k, R, S, _p(slot_of), _p(out["count"]), _p(out["rank_count"]),
+                     _p(out["cnt_src"]), _p(out["offset"]), _p(out["rank_offset"]),
+                     _p(out["row_of"]), _p(out["src_of"]), _p(cursor))
+    return out
+
+
+def pack(x, row_of, fill=0):
+    """O6.  x: [T, ...] any dtype, contiguous -> recv [T*k, ...]; untouched rows = fill."""
+    x = np.ascontiguousarray(x)
+    row_of = _i32(row_of)
+    T, k = row_of.shape
+    recv = np.full((T * k,) + x.shape[1:], fill, dtype=x.dtype)
+    row_bytes = x[0].nbytes if T else 0
+    lib().eeo_pack(T, k, ctypes.c_int64(row_bytes), _p(x), _p(row_of), _p(recv))
+    return recv
+
+
+def stub_scale(recv, dtype, N, offset, p2l, expert_scale):
+    """O7 scalar stub.  recv: [rows, H] float32 (dtype F32) or uint16 bf16 bits (BF16)."""
+    recv = np.ascontiguousarray(recv)
+    y = np.zeros_like(recv)
+    H = recv.shape[1]
+    p2l = _i32(p2l)
+    lib().eeo_stub_scale(int(N), H, p2l.size, dtype, _p(recv), _p(_i32(offset)), _p(p2l),
+                         _p(np.ascontiguousarray(expert_scale, np.float32)), _p(y))
+    return y
+
+
+def stub_dequant(q, scale, N, group):
+    """O7 fp8 stub -> bf16 bits [rows, H]."""
+    q = np.ascontiguousarray(q, np.uint8)
+    scale = np.ascontiguousarray(scale, np.float32)
+    y = np.zeros(q.shape, np.uint16)
+    lib().eeo_stub_dequant(int(N), q.shape[1], group, _p(q), _p(scale), _p(y))
+    return y
+
+
+def combine(y, y_dtype, w, row_of):
+    """O8 in double -> float64 [T, H]."""
+    y = np.ascontiguousarray(y)
+    w = np.ascontiguousarray(w, np.float32)
+    row_of = _i32(row_of)
+    T, k = row_of.shape
+    H = y.shape[1]
+    out = np.empty((T, H), np.float64)
+    lib().eeo_combine(T, k, H, y_dtype, _p(y), _p(w), _p(row_of), _p(out))
+    return out
+
+
+def combine_chain32(y, y_dtype, w, row_of):
+    """O8, fp32 fused-multiply-add chain in ascending j -> float32 [T, H]."""
+    y = np.ascontiguousarray(y)
+    w = np.ascontiguousarray(w, np.float32)
+    row_of = _i32(row_of)
+    T, k = row_of.shape
+    H = y.shape[1]
+    out = np.empty((T, H), np.float32)
+    lib().eeo_combine_chain32(T, k, H, y_dtype, _p(y), _p(w), _p(row_of), _p(out))
+    return out
+
+
+def bf16_to_f32(bits):
+    bits = np.ascontiguousarray(bits, np.uint16)
+    out = np.empty(bits.shape, np.float32)
+    lib().eeo_bf16_to_f32_array(ctypes.c_int64(bits.size), _p(bits), _p(out))
+    return out
+
+
+def f32_to_bf16(x):
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty(x.shape, np.uint16)
+    lib().eeo_f32_to_bf16_array(ctypes.c_int64(x.size), _p(x), _p(out))
+    return out
+
+
+def e4m3_to_f32(q):
+    q = np.ascontiguousarray(q, np.uint8)
+    out = np.empty(q.shape, np.float32)
+    lib().eeo_e4m3_to_f32_array(ctypes.c_int64(q.size), _p(q), _p(out))
+    return out
+
+
+def step_layout(topk_idx, p2l, active, E, R, S, S_prim, policy):
+    """O1-O5 in one call -> dict with slot_of, counters and every layout array."""
+    off, lst = tables(p2l, E, S, S_prim)
+    slot_of, n_unc, n_msk = map_pairs(topk_idx, off, lst, active, E, S, policy)
+    lay = layout(slot_of, R, S)
+    lay.update(slot_of=slot_of, n_uncovered=n_unc, n_masked=n_msk, l2p_off=off, l2p_list=lst,
+               N=int(lay["offset"][-1]))
+    return lay
