@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the dispatch/combine hot path on ONE MI355X.
+
+A step = eep_dispatch_layout + eep_dispatch + eep_combine over one synthetic
+DeepSeek-V3-shaped decode batch (T=4096 tokens of 32 virtual ranks, hidden 7168
+bf16, 256 experts, top-8, 8+1 slots per rank, all ranks live, identity expert:
+y aliases the receive buffer).  Inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line.  `value` is achieved GB/s = algorithmic bytes per step /
+time per step; `ms_per_step` carries the latency.  `roofline` describes the
+dominant kernel against the 8 TB/s HBM peak, `cpu_baseline` is the CPU oracle
+timed on this machine's host cores on the same workload.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(T, k, H, x_bytes, y_bytes, out_bytes, scale_row_bytes=0):
+    """Bytes the method must move per step: read each token row once and write
+    one row per routed pair (dispatch); read each expert-output row once and
+    write each token row once (combine); plus the per-pair metadata."""
+    pairs = T * k
+    dispatch = T * (H * x_bytes + scale_row_bytes) + pairs * (H * x_bytes + scale_row_bytes)
+    combine = pairs * H * y_bytes + T * H * out_bytes
+    # layout: read topk_idx, write slot_of/row_of/src_of; dispatch+combine: read row_of, topk_w
+    meta = pairs * 4 * 4 + pairs * 4 * 3
+    return dict(dispatch=dispatch + pairs * 4, combine=combine + pairs * 8, layout=pairs * 16,
+                total=dispatch + combine + meta)
+
+
+def time_events(stream, fn, reps):
+    import torch
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(reps):
+        fn()
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps  # ms
+
+
+def cpu_baseline(wl, bytes_total, budget_s=20.0):
+    """The oracle as it stands (single thread) on the same workload."""
+    import oracle
+    times = []
+    t_all = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < 10):
+        t0 = time.perf_counter()
+        lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim,
+                                 oracle.SPREAD)
+        recv = oracle.pack(wl.x, lay["row_of"])
+        oracle.combine(recv, oracle.BF16, wl.topk_w, lay["row_of"])
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > budget_s:
+            break
+    med = statistics.median(times)
+    return {"value": bytes_total / med / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "ms_per_step": med * 1e3,
+            "sample": f"{len(times)} full {wl.name} steps (T={wl.T}), median"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
+                    help="replay a captured hipGraph of the step (default) or launch eagerly")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (virtual EP ranks share one HBM); "
+                 "use --gpus 1")
+
+    import torch
+    from paper_2605_10670_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.decode()
+    T, k, H = wl.T, wl.k, wl.H
+    nbytes = algorithmic_bytes(T, k, H, 2, 2, 2)
+
+    ctx = binding.Context(num_ranks=wl.R, slots_per_rank=wl.S, primary_slots=wl.S_prim,
+                          num_logical=wl.E, max_tokens=T, topk=k, hidden=H, x_dtype="bf16",
+                          y_dtype="bf16", out_dtype="bf16")
+    stream = torch.cuda.Stream()
+    import numpy as np
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    idx, w = dev(wl.topk_idx), dev(wl.topk_w)
+    x = dev(wl.x.view(np.int16))
+    recv = torch.empty((T * k, H), dtype=torch.int16, device="cuda")
+    out = torch.empty((T, H), dtype=torch.int16, device="cuda")
+    torch.cuda.synchronize()
+    ctx.update_placement(wl.p2l, stream)
+    ctx.set_membership(wl.active, stream)
+
+    def layout():
+        ctx.dispatch_layout(idx, T, stream)
+
+    def dispatch():
+        ctx.dispatch(x, recv, T, stream=stream)
+
+    def combine():
+        ctx.combine(recv, w, out, T, stream=stream)   # identity expert: y aliases recv
+
+    def step():
+        layout()
+        dispatch()
+        combine()
+
+    step()
+    stream.synchronize()
+    graph = None
+    if args.mode == "graph":
+        ctx.graph_begin(stream)
+        step()
+        graph = ctx.graph_end(stream)
+        run = lambda: graph.launch(stream)
+    else:
+        run = step
+
+    for _ in range(args.warmup):
+        run()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms = time_events(stream, run, args.steps)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-call durations (HIP events on the launch stream, eager launches)
+    stage_ms = {}
+    for name, fn in (("layout", layout), ("dispatch", dispatch), ("combine", combine)):
+        for _ in range(5):
+            fn()
+        stream.synchronize()
+        stage_ms[name] = time_events(stream, fn, args.steps)
+    other_ms = None
+    if graph is not None:
+        other_ms = time_events(stream, step, args.steps)   # eager, for comparison
+        graph.destroy()
+
+    dom = max(("dispatch", "combine"), key=lambda n: stage_ms[n])
+    dom_kernel = {"dispatch": "k_pack", "combine": "k_combine"}[dom]
+    achieved = nbytes[dom] / (stage_ms[dom] * 1e-3) / 1e9
+    result = {
+        "metric": "dispatch+combine achieved HBM GB/s (algorithmic bytes / step time), "
+                  "DSV3 decode shape",
+        "value": nbytes["total"] / (ms * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "us_per_step": ms * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "dsv3-decode: T=4096 (32 ranks x 128), H=7168 bf16, E=256, top-8, "
+                               "8+1 slots/rank, all live, identity expert",
+                   "mode": args.mode, "step": "dispatch_layout + dispatch + combine",
+                   "algorithmic_bytes_per_step": nbytes["total"]},
+        "frac_of_hbm_peak": nbytes["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "wall_ms_per_step": wall_ms,
+        "stages_us": {n: v * 1e3 for n, v in stage_ms.items()},
+        "stages_gbs": {n: nbytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in stage_ms},
+        "eager_us_per_step": other_ms * 1e3 if other_ms is not None else None,
+        "roofline": {"bound": "hbm", "kernel": dom_kernel, "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None,
+                     "algorithmic_bytes_per_launch": nbytes[dom],
+                     "avg_launch_us": stage_ms[dom] * 1e3},
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl, nbytes["total"])
+    ctx.destroy()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

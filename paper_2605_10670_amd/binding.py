@@ -1,0 +1,226 @@
+"""ctypes binding of libeep.so (include/eep.h).  Argument marshalling only:
+every step of the path runs in the library's HIP kernels.  Device buffers are
+torch tensors (or raw integer addresses); streams are raw hipStream_t handles
+(`torch.cuda.Stream.cuda_stream`).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libeep.so")
+
+OK, ERR_INVALID_ARG, ERR_ALIGN, ERR_COVERAGE, ERR_HIP, ERR_STATE = 0, -1, -2, -3, -4, -5
+F32, BF16, FP8_E4M3 = 0, 1, 2
+SPREAD, FIRST_LIVE = 0, 1
+STUB_IDENTITY, STUB_SCALE, STUB_DEQUANT = 0, 1, 2
+DTYPES = {"f32": F32, "bf16": BF16, "fp8": FP8_E4M3}
+STUBS = {"identity": STUB_IDENTITY, "scale": STUB_SCALE, "dequant": STUB_DEQUANT}
+
+VIEW_FIELDS = ["active", "phys_to_logical", "l2p_off", "l2p_list", "slot_of", "row_of", "src_of",
+               "count", "offset", "rank_count", "rank_offset", "cnt_src", "status"]
+
+
+class EepError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__(f"{what}: {_strerror(code)} ({code})")
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "num_ranks", "slots_per_rank", "primary_slots", "num_logical", "max_tokens", "topk",
+        "hidden", "x_dtype", "y_dtype", "out_dtype", "scale_group", "policy", "strict_coverage")]
+
+
+class _View(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in VIEW_FIELDS]
+
+
+_lib = None
+
+
+def load():
+    """Load libeep.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; "
+                           "g.build()'` (hipcc, gfx950) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    sig = {
+        "eep_create": [ctypes.POINTER(_Config), ctypes.POINTER(vp)],
+        "eep_destroy": [vp],
+        "eep_set_membership": [vp, vp, vp],
+        "eep_update_placement": [vp, vp, vp],
+        "eep_dispatch_layout": [vp, vp, i32, vp],
+        "eep_dispatch": [vp, vp, vp, vp, vp, i32, vp],
+        "eep_combine": [vp, vp, vp, vp, i32, vp],
+        "eep_expert_stub": [vp, i32, vp, vp, vp, vp, i32, vp],
+        "eep_get_view": [vp, ctypes.POINTER(_View)],
+        "eep_read_view": [vp, i32, vp, i64, vp],
+        "eep_last_hip_error": [vp],
+        "eep_graph_begin": [vp, vp],
+        "eep_graph_end": [vp, vp, ctypes.POINTER(vp)],
+        "eep_graph_launch": [vp, vp],
+        "eep_graph_destroy": [vp],
+        "eep_graph_counters": [vp, ctypes.POINTER(i64 * 3)],
+    }
+    for name, argtypes in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = argtypes
+        fn.restype = ctypes.c_int
+    lib.eep_strerror.argtypes = [ctypes.c_int]
+    lib.eep_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _strerror(code):
+    return load().eep_strerror(code).decode()
+
+
+def _ptr(t):
+    """Device address of a torch tensor (must be contiguous), an int, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return None
+    return s if isinstance(s, int) else s.cuda_stream
+
+
+def _check(code, what, ctx=None):
+    if code != OK:
+        err = EepError(code, what)
+        if code == ERR_HIP and ctx is not None:
+            err.args = (err.args[0] + f" [hipError {load().eep_last_hip_error(ctx)}]",)
+        raise err
+
+
+class Graph:
+    def __init__(self, handle):
+        self._h = handle
+
+    def launch(self, stream):
+        _check(load().eep_graph_launch(self._h, _stream(stream)), "eep_graph_launch")
+
+    def counters(self):
+        c = (ctypes.c_int64 * 3)()
+        _check(load().eep_graph_counters(self._h, ctypes.byref(c)), "eep_graph_counters")
+        return dict(instantiations=c[0], exec_updates=c[1], launches=c[2])
+
+    def destroy(self):
+        if self._h:
+            load().eep_graph_destroy(self._h)
+            self._h = None
+
+
+class Context:
+    """One EP instance on the current GPU."""
+
+    def __init__(self, *, num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk,
+                 hidden, x_dtype="bf16", y_dtype="bf16", out_dtype="bf16", scale_group=None,
+                 policy=SPREAD, strict_coverage=True):
+        xd = DTYPES[x_dtype] if isinstance(x_dtype, str) else x_dtype
+        if scale_group is None:
+            scale_group = 128 if xd == FP8_E4M3 else 0
+        self.cfg = _Config(num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk,
+                           hidden, xd, DTYPES[y_dtype] if isinstance(y_dtype, str) else y_dtype,
+                           DTYPES[out_dtype] if isinstance(out_dtype, str) else out_dtype,
+                           scale_group, policy, 1 if strict_coverage else 0)
+        self._h = ctypes.c_void_p()
+        _check(load().eep_create(ctypes.byref(self.cfg), ctypes.byref(self._h)), "eep_create")
+        self.R, self.S, self.E, self.k = num_ranks, slots_per_rank, num_logical, topk
+        self.P = num_ranks * slots_per_rank
+        self.T_max = max_tokens
+
+    # -- table updates -------------------------------------------------------
+    def set_membership(self, active, stream=None):
+        a = np.ascontiguousarray(active, np.int32)
+        if a.size != self.R:
+            raise ValueError("active must have R entries")
+        _check(load().eep_set_membership(self._h, a.ctypes.data, _stream(stream)),
+               "eep_set_membership", self._h)
+
+    def update_placement(self, phys_to_logical, stream=None):
+        p = np.ascontiguousarray(phys_to_logical, np.int32)
+        if p.size != self.P:
+            raise ValueError("phys_to_logical must have P entries")
+        _check(load().eep_update_placement(self._h, p.ctypes.data, _stream(stream)),
+               "eep_update_placement", self._h)
+
+    # -- per-step calls ------------------------------------------------------
+    def dispatch_layout(self, topk_idx, T, stream=None):
+        _check(load().eep_dispatch_layout(self._h, _ptr(topk_idx), T, _stream(stream)),
+               "eep_dispatch_layout", self._h)
+
+    def dispatch(self, x, recv_x, T, x_scale=None, recv_scale=None, stream=None):
+        _check(load().eep_dispatch(self._h, _ptr(x), _ptr(x_scale), _ptr(recv_x),
+                                   _ptr(recv_scale), T, _stream(stream)), "eep_dispatch", self._h)
+
+    def combine(self, y, topk_w, out, T, stream=None):
+        _check(load().eep_combine(self._h, _ptr(y), _ptr(topk_w), _ptr(out), T, _stream(stream)),
+               "eep_combine", self._h)
+
+    def expert_stub(self, kind, recv_x, y, T, recv_scale=None, expert_scale=None, stream=None):
+        kind = STUBS[kind] if isinstance(kind, str) else kind
+        _check(load().eep_expert_stub(self._h, kind, _ptr(recv_x), _ptr(recv_scale),
+                                      _ptr(expert_scale), _ptr(y), T, _stream(stream)),
+               "eep_expert_stub", self._h)
+
+    # -- introspection -------------------------------------------------------
+    def view_pointers(self):
+        v = _View()
+        _check(load().eep_get_view(self._h, ctypes.byref(v)), "eep_get_view")
+        return {n: getattr(v, n) for n in VIEW_FIELDS}
+
+    def read(self, field, n, stream=None):
+        """Host copy (numpy int32[n]) of one view array, after waiting for `stream`."""
+        out = np.empty(n, np.int32)
+        _check(load().eep_read_view(self._h, VIEW_FIELDS.index(field), out.ctypes.data, n,
+                                    _stream(stream)), "eep_read_view", self._h)
+        return out
+
+    def read_layout(self, T, stream=None):
+        k, R, P = self.k, self.R, self.P
+        st = self.read("status", 4, stream)
+        return dict(
+            slot_of=self.read("slot_of", T * k).reshape(T, k),
+            row_of=self.read("row_of", T * k).reshape(T, k),
+            src_of=self.read("src_of", T * k), count=self.read("count", P),
+            offset=self.read("offset", P + 1), rank_count=self.read("rank_count", R),
+            rank_offset=self.read("rank_offset", R + 1),
+            cnt_src=self.read("cnt_src", R * P).reshape(R, P),
+            N=int(st[0]), n_uncovered=int(st[1]), n_masked=int(st[2]), version=int(st[3]))
+
+    # -- graphs --------------------------------------------------------------
+    def graph_begin(self, stream):
+        _check(load().eep_graph_begin(self._h, _stream(stream)), "eep_graph_begin", self._h)
+
+    def graph_end(self, stream):
+        g = ctypes.c_void_p()
+        _check(load().eep_graph_end(self._h, _stream(stream), ctypes.byref(g)), "eep_graph_end",
+               self._h)
+        return Graph(g)
+
+    def destroy(self):
+        if self._h:
+            load().eep_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,317 @@
+// C ABI of libeep: argument checks, context and table state, kernel launches.
+// See include/eep.h for the contract of every entry point.
+#include <new>
+
+#include "eep_internal.hpp"
+
+using namespace eep;
+
+namespace {
+
+int fail_hip(eep_ctx* c, hipError_t e) {
+  if (c) c->last_hip_error = (int)e;
+  return EEP_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Number of logical experts without a replica on an active rank (validity
+// condition 2 of Sec. 3.2), from host copies of the tables.
+int uncovered_experts(const eep_ctx* c, const int32_t* p2l, const int32_t* active) {
+  std::vector<char> live(c->E, 0);
+  for (int p = 0; p < c->P; ++p)
+    if (p2l[p] >= 0 && active[p / c->S] != 0) live[p2l[p]] = 1;
+  int missing = 0;
+  for (int e = 0; e < c->E; ++e) missing += !live[e];
+  return missing;
+}
+
+// Replica lists per logical expert in canonical order: primary slots first,
+// then redundant ones, each by ascending slot id.
+void build_csr(const eep_ctx* c, const int32_t* p2l, std::vector<int32_t>& off,
+               std::vector<int32_t>& list) {
+  off.assign(c->E + 1, 0);
+  list.assign(c->P, -1);
+  for (int p = 0; p < c->P; ++p)
+    if (p2l[p] >= 0) off[p2l[p] + 1]++;
+  for (int e = 0; e < c->E; ++e) off[e + 1] += off[e];
+  std::vector<int32_t> cur(off.begin(), off.end() - 1);
+  for (int pass = 0; pass < 2; ++pass)
+    for (int p = 0; p < c->P; ++p) {
+      bool redundant = (p % c->S) >= c->S_prim;
+      if (p2l[p] >= 0 && redundant == (pass == 1)) list[cur[p2l[p]]++] = p;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* eep_strerror(int code) {
+  switch (code) {
+    case EEP_OK: return "ok";
+    case EEP_ERR_INVALID_ARG: return "invalid argument";
+    case EEP_ERR_ALIGN: return "row size or pointer not 16-byte aligned";
+    case EEP_ERR_COVERAGE: return "a logical expert would have no live replica";
+    case EEP_ERR_HIP: return "HIP runtime error";
+    case EEP_ERR_STATE: return "call order violated";
+    default: return "unknown error";
+  }
+}
+
+int eep_last_hip_error(eep_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+int eep_create(const eep_config* cfg, eep_ctx** out) {
+  if (!out) return EEP_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!cfg) return EEP_ERR_INVALID_ARG;
+  const eep_config& f = *cfg;
+  if (f.num_ranks < 1 || f.slots_per_rank < 1 || f.primary_slots < 0 ||
+      f.primary_slots > f.slots_per_rank || f.num_logical < 1 || f.max_tokens < 0 || f.topk < 1 ||
+      f.topk > kMaxTopk || f.hidden < 1)
+    return EEP_ERR_INVALID_ARG;
+  if ((int64_t)f.num_ranks * f.slots_per_rank > (1 << 20) || f.num_logical > (1 << 20) ||
+      (int64_t)f.max_tokens * f.topk > (int64_t)1 << 30)
+    return EEP_ERR_INVALID_ARG;
+  auto dtype_ok = [](int d) { return d == EEP_F32 || d == EEP_BF16; };
+  if (!(dtype_ok(f.x_dtype) || f.x_dtype == EEP_FP8_E4M3) || !dtype_ok(f.y_dtype) ||
+      !dtype_ok(f.out_dtype))
+    return EEP_ERR_INVALID_ARG;
+  if (f.policy != EEP_SPREAD && f.policy != EEP_FIRST_LIVE) return EEP_ERR_INVALID_ARG;
+  if (f.x_dtype == EEP_FP8_E4M3) {
+    if (f.scale_group < 16 || f.scale_group % 16 != 0 || f.hidden % f.scale_group != 0)
+      return EEP_ERR_INVALID_ARG;
+  } else if (f.scale_group != 0) {
+    return EEP_ERR_INVALID_ARG;
+  }
+
+  eep_ctx* c = new (std::nothrow) eep_ctx();
+  if (!c) return EEP_ERR_INVALID_ARG;
+  c->cfg = f;
+  c->R = f.num_ranks;
+  c->S = f.slots_per_rank;
+  c->S_prim = f.primary_slots;
+  c->P = c->R * c->S;
+  c->E = f.num_logical;
+  c->k = f.topk;
+  c->H = f.hidden;
+  c->T_max = f.max_tokens;
+  c->x_row_bytes = (int64_t)c->H * dtype_bytes(f.x_dtype);
+  c->y_row_bytes = (int64_t)c->H * dtype_bytes(f.y_dtype);
+  c->out_row_bytes = (int64_t)c->H * dtype_bytes(f.out_dtype);
+  c->scale_row_bytes = f.x_dtype == EEP_FP8_E4M3 ? (int64_t)(c->H / f.scale_group) * 4 : 0;
+  c->version = 0;
+  c->layout_T = -1;
+  c->last_hip_error = 0;
+  c->slab = nullptr;
+  if (c->x_row_bytes % 16 || c->y_row_bytes % 16 || c->out_row_bytes % 16 ||
+      c->scale_row_bytes % 16) {
+    delete c;
+    return EEP_ERR_ALIGN;
+  }
+  Tiling g = make_tiling(c->T_max - c->T_max % c->R, c->R);
+  c->max_tiles = g.num_tiles > 0 ? g.num_tiles : 1;
+  // the map kernel keeps its tables in LDS; refuse shapes that do not fit 64 KiB
+  size_t lds = sizeof(int32_t) * ((size_t)2 * c->E + c->P + (size_t)c->P * kBitmapWords +
+                                  (size_t)2 * kTileTokens * c->k);
+  if (lds > 60 * 1024 || sizeof(int32_t) * ((size_t)2 * c->P + 1) > 60 * 1024) {
+    delete c;
+    return EEP_ERR_INVALID_ARG;
+  }
+
+  hipError_t e = hipGetDevice(&c->device);
+  if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
+
+  const int64_t pairs = (int64_t)c->T_max * c->k;
+  int64_t* n = c->field_ints;
+  n[EEP_V_ACTIVE] = c->R;
+  n[EEP_V_PHYS_TO_LOGICAL] = c->P;
+  n[EEP_V_L2P_OFF] = c->E + 1;
+  n[EEP_V_L2P_LIST] = c->P;
+  n[EEP_V_SLOT_OF] = pairs;
+  n[EEP_V_ROW_OF] = pairs;
+  n[EEP_V_SRC_OF] = pairs;
+  n[EEP_V_COUNT] = c->P;
+  n[EEP_V_OFFSET] = c->P + 1;
+  n[EEP_V_RANK_COUNT] = c->R;
+  n[EEP_V_RANK_OFFSET] = c->R + 1;
+  n[EEP_V_CNT_SRC] = (int64_t)c->R * c->P;
+  n[EEP_V_STATUS] = 4;
+  int32_t** field_ptr[EEP_V_NUM_FIELDS] = {
+      &c->active, &c->p2l,   &c->l2p_off, &c->l2p_list,   &c->slot_of,     &c->row_of, &c->src_of,
+      &c->count,  &c->offset, &c->rank_count, &c->rank_offset, &c->cnt_src, &c->status};
+  // carve one slab; every array starts on a 256-byte boundary
+  auto round_up = [](int64_t ints) { return (ints + 63) / 64 * 64; };
+  int64_t total = 0;
+  for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) total += round_up(n[i] > 0 ? n[i] : 1);
+  const int64_t n_tile = (int64_t)c->max_tiles * c->P;
+  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + round_up(1);
+  e = hipMalloc(&c->slab, (size_t)total * sizeof(int32_t));
+  if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
+  int32_t* cur = (int32_t*)c->slab;
+  for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) {
+    *field_ptr[i] = cur;
+    cur += round_up(n[i] > 0 ? n[i] : 1);
+  }
+  c->cnt_tile = cur;  cur += round_up(n_tile);
+  c->base_tile = cur; cur += round_up(n_tile);
+  c->blk_unc = cur;   cur += round_up(c->max_tiles);
+  c->blk_msk = cur;   cur += round_up(c->max_tiles);
+  c->tbl_version = cur;
+
+  // initial state: every rank live, every slot empty, nothing laid out
+  c->h_active.assign(c->R, 1);
+  c->h_p2l.assign(c->P, -1);
+  hipStream_t st = nullptr;
+  e = hipMemsetAsync(c->slab, 0, (size_t)total * sizeof(int32_t), st);
+  if (e == hipSuccess) e = launch_fill(c->active, 1, c->R, st);
+  if (e == hipSuccess) e = launch_fill(c->p2l, -1, c->P, st);
+  if (e == hipSuccess) e = launch_fill(c->l2p_list, -1, c->P, st);
+  if (e == hipSuccess) e = launch_fill(c->slot_of, -1, pairs, st);
+  if (e == hipSuccess) e = launch_fill(c->row_of, -1, pairs, st);
+  if (e == hipSuccess) e = launch_fill(c->src_of, -1, pairs, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) {
+    (void)hipFree(c->slab);
+    delete c;
+    return EEP_ERR_HIP;
+  }
+  *out = c;
+  return EEP_OK;
+}
+
+int eep_destroy(eep_ctx* ctx) {
+  if (!ctx) return EEP_OK;
+  hipError_t e = hipDeviceSynchronize();
+  hipError_t e2 = hipFree(ctx->slab);
+  delete ctx;
+  return (e == hipSuccess && e2 == hipSuccess) ? EEP_OK : EEP_ERR_HIP;
+}
+
+int eep_set_membership(eep_ctx* c, const int32_t* active_host, void* stream) {
+  if (!c || !active_host) return EEP_ERR_INVALID_ARG;
+  std::vector<int32_t> a(c->R);
+  for (int r = 0; r < c->R; ++r) a[r] = active_host[r] != 0 ? 1 : 0;
+  if (c->cfg.strict_coverage && uncovered_experts(c, c->h_p2l.data(), a.data()) > 0)
+    return EEP_ERR_COVERAGE;
+  hipError_t e = launch_patch(c->active, a.data(), c->R, c->tbl_version, c->version + 1,
+                              (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e);
+  c->h_active = a;
+  c->version += 1;
+  return EEP_OK;
+}
+
+int eep_update_placement(eep_ctx* c, const int32_t* p2l_host, void* stream) {
+  if (!c || !p2l_host) return EEP_ERR_INVALID_ARG;
+  for (int p = 0; p < c->P; ++p)
+    if (p2l_host[p] < -1 || p2l_host[p] >= c->E) return EEP_ERR_INVALID_ARG;
+  if (c->cfg.strict_coverage && uncovered_experts(c, p2l_host, c->h_active.data()) > 0)
+    return EEP_ERR_COVERAGE;
+  std::vector<int32_t> off, list;
+  build_csr(c, p2l_host, off, list);
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_patch(c->p2l, p2l_host, c->P, nullptr, 0, st);
+  if (e == hipSuccess) e = launch_patch(c->l2p_off, off.data(), c->E + 1, nullptr, 0, st);
+  if (e == hipSuccess)
+    e = launch_patch(c->l2p_list, list.data(), c->P, c->tbl_version, c->version + 1, st);
+  if (e != hipSuccess) return fail_hip(c, e);
+  c->h_p2l.assign(p2l_host, p2l_host + c->P);
+  c->version += 1;
+  return EEP_OK;
+}
+
+int eep_dispatch_layout(eep_ctx* c, const int32_t* topk_idx, int32_t T, void* stream) {
+  if (!c || T < 0 || T > c->T_max || T % c->R != 0) return EEP_ERR_INVALID_ARG;
+  if (T > 0 && !topk_idx) return EEP_ERR_INVALID_ARG;
+  hipError_t e = launch_layout(c, topk_idx, T, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e);
+  c->layout_T = T;
+  return EEP_OK;
+}
+
+int eep_dispatch(eep_ctx* c, const void* x, const float* x_scale, void* recv_x, float* recv_scale,
+                 int32_t T, void* stream) {
+  if (!c || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T) return EEP_ERR_STATE;
+  if (T == 0) return EEP_OK;
+  if (!x || !recv_x) return EEP_ERR_INVALID_ARG;
+  const bool fp8 = c->cfg.x_dtype == EEP_FP8_E4M3;
+  if (fp8 != (x_scale != nullptr) || fp8 != (recv_scale != nullptr)) return EEP_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(recv_x) || !aligned16(x_scale) || !aligned16(recv_scale))
+    return EEP_ERR_ALIGN;
+  hipError_t e = launch_pack(c, x, x_scale, recv_x, recv_scale, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_combine(eep_ctx* c, const void* y, const float* topk_w, void* out, int32_t T,
+                void* stream) {
+  if (!c || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T) return EEP_ERR_STATE;
+  if (T == 0) return EEP_OK;
+  if (!y || !topk_w || !out) return EEP_ERR_INVALID_ARG;
+  if (!aligned16(y) || !aligned16(out)) return EEP_ERR_ALIGN;
+  hipError_t e = launch_combine(c, y, topk_w, out, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_expert_stub(eep_ctx* c, int32_t kind, const void* recv_x, const float* recv_scale,
+                    const float* expert_scale, void* y, int32_t T, void* stream) {
+  if (!c || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T) return EEP_ERR_STATE;
+  if (T == 0) return EEP_OK;
+  if (!recv_x || !y) return EEP_ERR_INVALID_ARG;
+  if (!aligned16(recv_x) || !aligned16(y)) return EEP_ERR_ALIGN;
+  switch (kind) {
+    case EEP_STUB_IDENTITY:
+      if (c->cfg.x_dtype != c->cfg.y_dtype) return EEP_ERR_INVALID_ARG;
+      break;
+    case EEP_STUB_SCALE:
+      if (c->cfg.x_dtype != c->cfg.y_dtype || !expert_scale) return EEP_ERR_INVALID_ARG;
+      break;
+    case EEP_STUB_DEQUANT:
+      if (c->cfg.x_dtype != EEP_FP8_E4M3 || c->cfg.y_dtype != EEP_BF16 || !recv_scale)
+        return EEP_ERR_INVALID_ARG;
+      break;
+    default:
+      return EEP_ERR_INVALID_ARG;
+  }
+  hipError_t e =
+      launch_stub(c, kind, recv_x, recv_scale, expert_scale, y, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_get_view(eep_ctx* c, eep_view* out) {
+  if (!c || !out) return EEP_ERR_INVALID_ARG;
+  out->active = c->active;
+  out->phys_to_logical = c->p2l;
+  out->l2p_off = c->l2p_off;
+  out->l2p_list = c->l2p_list;
+  out->slot_of = c->slot_of;
+  out->row_of = c->row_of;
+  out->src_of = c->src_of;
+  out->count = c->count;
+  out->offset = c->offset;
+  out->rank_count = c->rank_count;
+  out->rank_offset = c->rank_offset;
+  out->cnt_src = c->cnt_src;
+  out->status = c->status;
+  return EEP_OK;
+}
+
+int eep_read_view(eep_ctx* c, int32_t field, int32_t* host_dst, int64_t n, void* stream) {
+  if (!c || field < 0 || field >= EEP_V_NUM_FIELDS || n < 0) return EEP_ERR_INVALID_ARG;
+  if (n > c->field_ints[field]) return EEP_ERR_INVALID_ARG;
+  if (n == 0) return EEP_OK;
+  if (!host_dst) return EEP_ERR_INVALID_ARG;
+  const int32_t* src[EEP_V_NUM_FIELDS] = {c->active, c->p2l,    c->l2p_off,    c->l2p_list,
+                                          c->slot_of, c->row_of, c->src_of,     c->count,
+                                          c->offset,  c->rank_count, c->rank_offset, c->cnt_src,
+                                          c->status};
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e == hipSuccess)
+    e = hipMemcpy(host_dst, src[field], (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+}  // extern "C"

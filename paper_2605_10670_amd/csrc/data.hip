@@ -1,0 +1,318 @@
+// The bandwidth-bound half of the step: pack (dispatch), the expert stand-ins,
+// and the weighted gather-reduce (combine).
+//
+// Paper: Fig. 7 (dispatch writes one token row per (token, destination)),
+// Sec. 4.1 (combine reduces the expert outputs), Sec. 6.2 (dispatch and
+// combine dominate the cost of EP serving).  Nothing here is a contraction:
+// every kernel is bound by HBM traffic, so the design rules are 16-byte
+// accesses, whole 64-lane wavefronts on contiguous 1 KiB spans, each input byte
+// read once, and enough independent loads in flight per lane.
+#include "eep_internal.hpp"
+
+namespace eep {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// pack: recv[row_of[t, j]] = x[t].  One workgroup per token reads the row once
+// (U 16-byte vectors per thread per pass) and stores it to its k rows.
+// ---------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(256) void k_pack(const u32x4* __restrict__ x,
+                                              u32x4* __restrict__ recv,
+                                              const u32x4* __restrict__ x_scale,
+                                              u32x4* __restrict__ recv_scale,
+                                              const int32_t* __restrict__ row_of, int k,
+                                              int row_vecs, int scale_vecs) {
+  const int t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int nthr = blockDim.x;
+  const int32_t* rows = row_of + (int64_t)t * k;
+  const u32x4* src = x + (int64_t)t * row_vecs;
+  for (int v0 = 0; v0 < row_vecs; v0 += nthr * U) {
+    u32x4 buf[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int v = v0 + u * nthr + tid;
+      if (v < row_vecs) buf[u] = __builtin_nontemporal_load(&src[v]);
+    }
+    for (int j = 0; j < k; ++j) {
+      int row = rows[j];
+      if (row < 0) continue;
+      u32x4* dst = recv + (int64_t)row * row_vecs;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int v = v0 + u * nthr + tid;
+        if (v < row_vecs) __builtin_nontemporal_store(buf[u], &dst[v]);
+      }
+    }
+  }
+  if (scale_vecs > 0) {
+    for (int v = tid; v < scale_vecs; v += nthr) {
+      u32x4 s = x_scale[(int64_t)t * scale_vecs + v];
+      for (int j = 0; j < k; ++j) {
+        int row = rows[j];
+        if (row >= 0) recv_scale[(int64_t)row * scale_vecs + v] = s;
+      }
+    }
+  }
+}
+
+hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
+                       float* recv_scale, int T, hipStream_t st) {
+  if (T == 0) return hipSuccess;
+  int row_vecs = (int)(c->x_row_bytes / 16);
+  int scale_vecs = (int)(c->scale_row_bytes / 16);
+  // threads per token: enough that each thread moves <= 4 vectors per pass
+  int threads = 256;
+  if (row_vecs <= 64 * 4) threads = 64;
+  else if (row_vecs <= 128 * 4) threads = 128;
+  hipLaunchKernelGGL(k_pack<4>, dim3(T), dim3(threads), 0, st, (const u32x4*)x, (u32x4*)recv_x,
+                     (const u32x4*)x_scale, (u32x4*)recv_scale, c->row_of, c->k, row_vecs,
+                     scale_vecs);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// number formats
+// ---------------------------------------------------------------------------
+__device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// binary32 -> bfloat16 bits, round to nearest even, NaN stays (quiet) NaN
+__device__ inline uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// OCP e4m3fn byte -> binary32 (1-4-3, bias 7, no inf, S.1111.111 = NaN)
+__device__ inline float e4m3_to_f32(uint32_t q) {
+  uint32_t mag = q & 0x7fu;
+  uint32_t sign = (q & 0x80u) << 24;
+  uint32_t bits;
+  if (mag == 0x7fu) bits = 0x7fc00000u;
+  else if (mag >= 8u) bits = (mag << 20) + (120u << 23);
+  else bits = __float_as_uint((float)mag * 0x1p-9f);
+  return __uint_as_float(bits | sign);
+}
+
+// ---------------------------------------------------------------------------
+// combine: out[t] = sum_j w[t,j] * y[row_of[t,j]], fp32 fused multiply-add chain
+// in ascending j.  One workgroup per token; a thread owns 16-byte columns of
+// the row and issues the k row loads of a column back to back.
+// ---------------------------------------------------------------------------
+template <bool Y_BF16>
+struct YVec {
+  static constexpr int kElems = Y_BF16 ? 8 : 4;
+};
+
+template <bool Y_BF16>
+__device__ inline void accumulate(float (&acc)[YVec<Y_BF16>::kElems], u32x4 v, float w) {
+  if constexpr (Y_BF16) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] = fmaf(w, bf16_lo(v[i]), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(w, bf16_hi(v[i]), acc[2 * i + 1]);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = fmaf(w, __uint_as_float(v[i]), acc[i]);
+  }
+}
+
+template <bool Y_BF16, bool OUT_BF16>
+__device__ inline void store_out(void* out_row, int v, const float (&acc)[YVec<Y_BF16>::kElems]) {
+  if constexpr (Y_BF16 && OUT_BF16) {
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
+    __builtin_nontemporal_store(o, (u32x4*)out_row + v);
+  } else if constexpr (Y_BF16 && !OUT_BF16) {
+    f32x4 a = {acc[0], acc[1], acc[2], acc[3]}, b = {acc[4], acc[5], acc[6], acc[7]};
+    __builtin_nontemporal_store(a, (f32x4*)out_row + 2 * v);
+    __builtin_nontemporal_store(b, (f32x4*)out_row + 2 * v + 1);
+  } else if constexpr (!Y_BF16 && OUT_BF16) {
+    u32x2 o = {pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3])};
+    __builtin_nontemporal_store(o, (u32x2*)out_row + v);
+  } else {
+    f32x4 a = {acc[0], acc[1], acc[2], acc[3]};
+    __builtin_nontemporal_store(a, (f32x4*)out_row + v);
+  }
+}
+
+template <bool Y_BF16, bool OUT_BF16, int K>
+__global__ __launch_bounds__(256) void k_combine(const u32x4* __restrict__ y,
+                                                 const float* __restrict__ topk_w,
+                                                 const int32_t* __restrict__ row_of,
+                                                 void* __restrict__ out, int k, int row_vecs,
+                                                 int64_t out_row_bytes) {
+  constexpr int NE = YVec<Y_BF16>::kElems;
+  const int t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int nthr = blockDim.x;
+  const int32_t* rows = row_of + (int64_t)t * k;
+  const float* ws = topk_w + (int64_t)t * k;
+  void* out_row = (char*)out + (int64_t)t * out_row_bytes;
+
+  if constexpr (K > 0) {
+    // fast path: compile-time k and every pair routed -> no branch between loads
+    int r[K];
+    float w[K];
+    bool all = true;
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      r[j] = rows[j];
+      w[j] = ws[j];
+      all &= (r[j] >= 0);
+    }
+    if (all) {
+      for (int v = tid; v < row_vecs; v += nthr) {
+        u32x4 d[K];
+#pragma unroll
+        for (int j = 0; j < K; ++j)
+          d[j] = __builtin_nontemporal_load(&y[(int64_t)r[j] * row_vecs + v]);
+        float acc[NE];
+#pragma unroll
+        for (int i = 0; i < NE; ++i) acc[i] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < K; ++j) accumulate<Y_BF16>(acc, d[j], w[j]);
+        store_out<Y_BF16, OUT_BF16>(out_row, v, acc);
+      }
+      return;
+    }
+  }
+  for (int v = tid; v < row_vecs; v += nthr) {
+    float acc[NE];
+#pragma unroll
+    for (int i = 0; i < NE; ++i) acc[i] = 0.0f;
+    for (int j = 0; j < k; ++j) {
+      int row = rows[j];
+      if (row < 0) continue;
+      u32x4 d = __builtin_nontemporal_load(&y[(int64_t)row * row_vecs + v]);
+      accumulate<Y_BF16>(acc, d, ws[j]);
+    }
+    store_out<Y_BF16, OUT_BF16>(out_row, v, acc);
+  }
+}
+
+template <bool Y_BF16, bool OUT_BF16>
+static hipError_t launch_combine_t(eep_ctx* c, const void* y, const float* w, void* out, int T,
+                                   hipStream_t st) {
+  int row_vecs = (int)(c->y_row_bytes / 16);
+  int threads = 256;
+  if (row_vecs <= 64) threads = 64;
+  else if (row_vecs <= 128) threads = 128;
+  dim3 grid(T), block(threads);
+  if (c->k == 8)
+    hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 8>), grid, block, 0, st, (const u32x4*)y, w,
+                       c->row_of, out, c->k, row_vecs, c->out_row_bytes);
+  else
+    hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 0>), grid, block, 0, st, (const u32x4*)y, w,
+                       c->row_of, out, c->k, row_vecs, c->out_row_bytes);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine(eep_ctx* c, const void* y, const float* w, void* out, int T,
+                          hipStream_t st) {
+  if (T == 0) return hipSuccess;
+  bool yb = c->cfg.y_dtype == EEP_BF16, ob = c->cfg.out_dtype == EEP_BF16;
+  if (yb && ob) return launch_combine_t<true, true>(c, y, w, out, T, st);
+  if (yb && !ob) return launch_combine_t<true, false>(c, y, w, out, T, st);
+  if (!yb && ob) return launch_combine_t<false, true>(c, y, w, out, T, st);
+  return launch_combine_t<false, false>(c, y, w, out, T, st);
+}
+
+// ---------------------------------------------------------------------------
+// expert stand-ins (outside the measured path): one workgroup per receive row,
+// rows >= N (read from device memory) are skipped.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_stub_copy(const u32x4* __restrict__ recv,
+                                                   u32x4* __restrict__ y,
+                                                   const int32_t* __restrict__ status,
+                                                   int row_vecs) {
+  const int row = blockIdx.x;
+  if (row >= status[0]) return;
+  for (int v = threadIdx.x; v < row_vecs; v += blockDim.x)
+    y[(int64_t)row * row_vecs + v] = recv[(int64_t)row * row_vecs + v];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_stub_scale(
+    const u32x4* __restrict__ recv, u32x4* __restrict__ y, const int32_t* __restrict__ status,
+    const int32_t* __restrict__ src_of, const int32_t* __restrict__ slot_of,
+    const int32_t* __restrict__ p2l, const float* __restrict__ expert_scale, int row_vecs) {
+  const int row = blockIdx.x;
+  if (row >= status[0]) return;
+  const int e = p2l[slot_of[src_of[row]]];
+  const float s = e >= 0 ? expert_scale[e] : 0.0f;
+  for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) {
+    u32x4 d = recv[(int64_t)row * row_vecs + v];
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if constexpr (BF16) o[i] = pack_bf16x2(s * bf16_lo(d[i]), s * bf16_hi(d[i]));
+      else o[i] = __float_as_uint(s * __uint_as_float(d[i]));
+    }
+    y[(int64_t)row * row_vecs + v] = o;
+  }
+}
+
+// 16 fp8 codes in, 16 bf16 out per thread step; all 16 share one scale
+// (group is a multiple of 16).
+__global__ __launch_bounds__(256) void k_stub_dequant(const u32x4* __restrict__ q,
+                                                      const float* __restrict__ scale,
+                                                      u32x4* __restrict__ y,
+                                                      const int32_t* __restrict__ status,
+                                                      int row_vecs, int group, int groups_per_row) {
+  const int row = blockIdx.x;
+  if (row >= status[0]) return;
+  for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) {
+    u32x4 d = q[(int64_t)row * row_vecs + v];
+    float sc = scale[(int64_t)row * groups_per_row + (v * 16) / group];
+    u32x4 o[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float f0 = sc * e4m3_to_f32(d[i] & 0xffu);
+      float f1 = sc * e4m3_to_f32((d[i] >> 8) & 0xffu);
+      float f2 = sc * e4m3_to_f32((d[i] >> 16) & 0xffu);
+      float f3 = sc * e4m3_to_f32(d[i] >> 24);
+      o[i >> 1][(i & 1) * 2] = pack_bf16x2(f0, f1);
+      o[i >> 1][(i & 1) * 2 + 1] = pack_bf16x2(f2, f3);
+    }
+    y[((int64_t)row * row_vecs + v) * 2] = o[0];
+    y[((int64_t)row * row_vecs + v) * 2 + 1] = o[1];
+  }
+}
+
+hipError_t launch_stub(eep_ctx* c, int kind, const void* recv_x, const float* recv_scale,
+                       const float* expert_scale, void* y, int T, hipStream_t st) {
+  int64_t rows = (int64_t)T * c->k;
+  if (rows == 0) return hipSuccess;
+  int row_vecs = (int)(c->x_row_bytes / 16);
+  dim3 grid((unsigned)rows), block(256);
+  if (kind == EEP_STUB_IDENTITY) {
+    hipLaunchKernelGGL(k_stub_copy, grid, block, 0, st, (const u32x4*)recv_x, (u32x4*)y,
+                       c->status, row_vecs);
+  } else if (kind == EEP_STUB_SCALE) {
+    if (c->cfg.x_dtype == EEP_BF16)
+      hipLaunchKernelGGL(k_stub_scale<true>, grid, block, 0, st, (const u32x4*)recv_x, (u32x4*)y,
+                         c->status, c->src_of, c->slot_of, c->p2l, expert_scale, row_vecs);
+    else
+      hipLaunchKernelGGL(k_stub_scale<false>, grid, block, 0, st, (const u32x4*)recv_x,
+                         (u32x4*)y, c->status, c->src_of, c->slot_of, c->p2l, expert_scale,
+                         row_vecs);
+  } else {
+    hipLaunchKernelGGL(k_stub_dequant, grid, block, 0, st, (const u32x4*)recv_x, recv_scale,
+                       (u32x4*)y, c->status, row_vecs, c->cfg.scale_group,
+                       c->H / c->cfg.scale_group);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace eep

@@ -1,0 +1,84 @@
+// Internal declarations shared by the HIP sources of libeep (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "eep.h"
+
+namespace eep {
+
+// Tokens of one layout tile never exceed this; a tile never straddles two
+// source ranks.  128 tokens = 4 bitmap words per slot.
+constexpr int kTileTokens = 128;
+constexpr int kBitmapWords = kTileTokens / 32;
+constexpr int kMaxTopk = 32;
+constexpr int kPatchInts = 512;  // ints carried by value in one table-patch launch
+
+struct Tiling {
+  int tokens_per_rank;  // T / R
+  int tiles_per_rank;   // nt
+  int tile_tokens;      // TT <= kTileTokens
+  int num_tiles;        // NB = R * nt
+};
+
+inline Tiling make_tiling(int T, int R) {
+  Tiling g;
+  g.tokens_per_rank = T / R;
+  g.tiles_per_rank = (g.tokens_per_rank + kTileTokens - 1) / kTileTokens;
+  if (g.tiles_per_rank < 1) g.tiles_per_rank = 1;
+  g.tile_tokens = (g.tokens_per_rank + g.tiles_per_rank - 1) / g.tiles_per_rank;
+  g.num_tiles = (T > 0) ? R * g.tiles_per_rank : 0;
+  return g;
+}
+
+inline int dtype_bytes(int dt) { return dt == EEP_F32 ? 4 : dt == EEP_BF16 ? 2 : 1; }
+
+struct PatchChunk {
+  int32_t v[kPatchInts];
+};
+
+}  // namespace eep
+
+struct eep_ctx {
+  eep_config cfg;
+  int R, S, S_prim, P, E, k, H, T_max;
+  int64_t x_row_bytes, y_row_bytes, out_row_bytes, scale_row_bytes;
+  int device;
+  int max_tiles;
+
+  void* slab;  // the one device allocation everything below points into
+  // tables (fixed addresses, contents patched in place)
+  int32_t *active, *p2l, *l2p_off, *l2p_list, *tbl_version;
+  // per-step layout results
+  int32_t *slot_of, *row_of, *src_of, *count, *offset, *rank_count, *rank_offset, *cnt_src, *status;
+  // per-step scratch
+  int32_t *cnt_tile, *base_tile, *blk_unc, *blk_msk;
+
+  // host shadows of the tables (coverage is validated without touching the GPU)
+  std::vector<int32_t> h_active, h_p2l;
+  int32_t version;
+  int layout_T;  // T of the last dispatch_layout, -1 if none yet
+  int last_hip_error;
+  int64_t field_ints[EEP_V_NUM_FIELDS];
+};
+
+namespace eep {
+
+// layout.hip
+hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st);
+// data.hip
+hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
+                       float* recv_scale, int T, hipStream_t st);
+hipError_t launch_combine(eep_ctx* c, const void* y, const float* w, void* out, int T,
+                          hipStream_t st);
+hipError_t launch_stub(eep_ctx* c, int kind, const void* recv_x, const float* recv_scale,
+                       const float* expert_scale, void* y, int T, hipStream_t st);
+// tables.hip
+hipError_t launch_patch(int32_t* dst, const int32_t* src_host, int n, int32_t* version_dst,
+                        int32_t version, hipStream_t st);
+hipError_t launch_fill(int32_t* dst, int32_t value, int64_t n, hipStream_t st);
+
+}  // namespace eep

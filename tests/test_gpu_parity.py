@@ -1,0 +1,199 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Integer results and moved bytes must be bit-exact; combine
+outputs must meet the 1e-3 gate against the fp64 oracle and be bit-equal to the
+oracle's fp32 ascending fused-multiply-add chain."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_10670_amd import binding, synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+ODT = {"f32": 0, "bf16": 1}
+
+
+def oracle_step(oracle, wl, policy=0, p2l=None, active=None):
+    p2l = wl.p2l if p2l is None else p2l
+    active = wl.active if active is None else active
+    lay = oracle.step_layout(wl.topk_idx, p2l, active, wl.E, wl.R, wl.S, wl.S_prim, policy)
+    recv = oracle.pack(wl.x, lay["row_of"])
+    recv_scale = oracle.pack(wl.x_scale, lay["row_of"]) if wl.x_scale is not None else None
+    N = lay["N"]
+    if wl.stub == "identity":
+        y = recv
+    elif wl.stub == "scale":
+        y = oracle.stub_scale(recv, ODT[wl.x_dtype], N, lay["offset"], p2l, wl.expert_scale)
+    else:
+        y = oracle.stub_dequant(recv, recv_scale, N, 128)
+    out64 = oracle.combine(y, ODT[wl.y_dtype], wl.topk_w, lay["row_of"])
+    chain = oracle.combine_chain32(y, ODT[wl.y_dtype], wl.topk_w, lay["row_of"])
+    chain_bits = chain.view(np.uint32) if wl.out_dtype == "f32" else oracle.f32_to_bf16(chain)
+    return dict(lay=lay, recv=recv, recv_scale=recv_scale, y=y, out64=out64, chain_bits=chain_bits)
+
+
+def run_and_compare(oracle, wl, policy=binding.SPREAD, strict=True):
+    ctx = gu.make_context(wl, policy=policy, strict=strict)
+    try:
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        dev = gu.DeviceStep(ctx, wl)
+        dev.step()
+        dev.sync()
+        ref = oracle_step(oracle, wl, policy)
+        got = ctx.read_layout(wl.T)
+        gu.assert_layout_equal(got, ref["lay"], wl.T, wl.k)
+        N = got["N"]
+        recv = gu.to_host(dev.recv, gu.NP_OF[wl.x_dtype])
+        assert np.array_equal(recv[:N].view(np.uint8), ref["recv"][:N].view(np.uint8)), "packed rows"
+        if wl.stub != "identity":
+            assert (recv[N:].view(np.uint8) == 0).all(), "rows past N were written"
+        if wl.x_scale is not None:
+            rs = dev.recv_scale.cpu().numpy()
+            assert np.array_equal(rs[:N].view(np.uint32), ref["recv_scale"][:N].view(np.uint32))
+        if wl.stub != "identity":
+            y = gu.to_host(dev.y, gu.NP_OF[wl.y_dtype])
+            assert np.array_equal(y[:N].view(np.uint8), ref["y"][:N].view(np.uint8)), "stub rows"
+        out = gu.to_host(dev.out, gu.NP_OF[wl.out_dtype])
+        bits = out.view(np.uint32) if wl.out_dtype == "f32" else out
+        gu.check_combine(out, wl.out_dtype, ref["out64"], None)
+        assert np.array_equal(bits, ref["chain_bits"]), "combine != fp32 ascending fma chain"
+        return got, ref
+    finally:
+        ctx.destroy()
+
+
+@pytest.mark.parametrize("variant", ["a", "c"])
+@pytest.mark.parametrize("policy", [binding.SPREAD, binding.FIRST_LIVE])
+def test_tiny_step(oracle, variant, policy):
+    wl = synth.tiny(variant)
+    got, ref = run_and_compare(oracle, wl, policy)
+    assert got["N"] == wl.T * wl.k
+    if variant == "c":
+        assert got["rank_count"][2] == 0          # the failed rank receives nothing
+        # closed form: y = s[e]*x  =>  out = (sum_j w_j s[e_j]) x, mask-independent
+        want = ((wl.topk_w.astype(np.float64) * wl.expert_scale[wl.topk_idx]).sum(1)[:, None]
+                * wl.x.astype(np.float64))
+        np.testing.assert_allclose(ref["out64"], want, rtol=1e-6, atol=1e-6)
+
+
+def test_tiny_infeasible_coverage(oracle):
+    """4+1 slots, rank 2 failed: 15 live slots < 16 experts (pigeonhole)."""
+    wl = synth.tiny("b")
+    ctx = gu.make_context(wl, strict=True)
+    try:
+        ctx.update_placement(wl.p2l)
+        with pytest.raises(binding.EepError) as ei:
+            ctx.set_membership(wl.active)
+        assert ei.value.code == binding.ERR_COVERAGE
+        # refused update left the tables alone: all ranks still live
+        assert ctx.read("active", wl.R).tolist() == [1] * wl.R
+    finally:
+        ctx.destroy()
+    got, ref = run_and_compare(oracle, wl, strict=False)
+    assert got["n_uncovered"] == int((wl.topk_idx == 11).sum()) > 0
+    assert got["N"] + got["n_uncovered"] + got["n_masked"] == wl.T * wl.k
+
+
+@pytest.mark.parametrize("T", [0, 32, 96, 4128, 4192])
+def test_decode_shape_ragged_sizes(oracle, T):
+    """T/R = 0, 1, 3, 129 and 131 tokens per rank: empty input, tiles smaller
+    than a wavefront, and ranks split into two ragged tiles (65+64, 66+65)."""
+    wl = synth.decode(T=T, H=512)
+    got, _ = run_and_compare(oracle, wl)
+    assert got["N"] == T * wl.k
+
+
+def test_masked_repeated_and_out_of_range_indices(oracle):
+    wl = synth.decode(T=256, H=256)
+    rng = np.random.default_rng(5)
+    idx = wl.topk_idx.copy()
+    idx[rng.random(idx.shape) < 0.05] = -1
+    idx[rng.random(idx.shape) < 0.02] = wl.E + 3
+    rep = rng.random(idx.shape[0]) < 0.2
+    idx[rep, 5] = idx[rep, 1]                       # a repeated expert inside a token
+    idx[7, :] = -1                                  # a token with nothing routed
+    wl.topk_idx = idx
+    got, ref = run_and_compare(oracle, wl)
+    assert got["n_masked"] > 0 and got["N"] + got["n_masked"] == wl.T * wl.k
+    assert (ref["out64"][7] == 0).all()
+
+
+@pytest.mark.parametrize("dtypes", [("f32", "f32", "f32", "scale"), ("bf16", "bf16", "f32", "scale"),
+                                    ("f32", "f32", "bf16", "identity"),
+                                    ("bf16", "bf16", "bf16", "scale")])
+@pytest.mark.parametrize("k", [1, 2, 6, 8])
+def test_dtype_and_topk_matrix(oracle, dtypes, k):
+    xd, yd, od, stub = dtypes
+    rng = np.random.default_rng(17 + k)
+    T, H, E, R, sp, sr = 192, 384, 24, 6, 4, 2
+    x32 = rng.standard_normal((T, H), dtype=np.float32)
+    x = x32 if xd == "f32" else synth.f32_to_bf16_bits(x32)
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    failed = (4,)
+    pref = synth.preferred_placement(R, sp, sr)
+    p2l = synth.repaired_placement(pref, failed, R, sp, sr)
+    wl = synth.Workload("matrix", T, H, E, k, R, sp, sr, xd, yd, od, stub, failed, idx, w, x, p2l,
+                        synth.active_mask(R, failed),
+                        expert_scale=(0.25 + rng.random(E)).astype(np.float32))
+    got, _ = run_and_compare(oracle, wl)
+    assert got["rank_count"][4] == 0
+
+
+def test_prefill_fp8_reduced(oracle):
+    wl = synth.prefill_fp8(T=1024, H=1024)
+    got, _ = run_and_compare(oracle, wl)
+    assert got["rank_count"][7] == 0 and got["rank_count"][20] == 0
+
+
+def test_decode_full_size(oracle):
+    """DeepSeek-V3 decode shape at full size, every output compared."""
+    wl = synth.decode()
+    got, ref = run_and_compare(oracle, wl)
+    assert got["N"] == 4096 * 8
+    # identity expert and softmax weights: out ~= x
+    x = gu.bf16_to_f64(wl.x)
+    assert np.abs(ref["out64"] - x).max() <= 1e-5 * np.abs(x).max()
+
+
+def test_decode_failed_rank_zipf_full_size(oracle):
+    wl = synth.decode_failed_zipf()
+    got, _ = run_and_compare(oracle, wl)
+    assert got["rank_count"][13] == 0 and got["N"] == 4096 * 8
+    S = wl.S
+    hot = got["count"].argsort()[::-1][:8]
+    assert all(p % S == S - 1 for p in hot)        # hottest slots are redundant replicas
+
+
+def test_call_order_and_argument_errors():
+    wl = synth.decode(T=64, H=256)
+    ctx = gu.make_context(wl)
+    try:
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        dev = gu.DeviceStep(ctx, wl)
+        with pytest.raises(binding.EepError) as ei:
+            dev.dispatch()                          # no layout yet
+        assert ei.value.code == binding.ERR_STATE
+        with pytest.raises(binding.EepError) as ei:
+            ctx.dispatch_layout(dev.idx, 65)        # not a multiple of R
+        assert ei.value.code == binding.ERR_INVALID_ARG
+        with pytest.raises(binding.EepError) as ei:
+            ctx.dispatch_layout(dev.idx, 128)       # > T_max
+        assert ei.value.code == binding.ERR_INVALID_ARG
+        dev.layout()
+        with pytest.raises(binding.EepError) as ei:
+            ctx.dispatch(dev.x.data_ptr() + 2, dev.recv, wl.T)
+        assert ei.value.code == binding.ERR_ALIGN
+        bad = wl.p2l.copy()
+        bad[0] = wl.E
+        with pytest.raises(binding.EepError) as ei:
+            ctx.update_placement(bad)
+        assert ei.value.code == binding.ERR_INVALID_ARG
+        dev.step()
+        dev.sync()
+    finally:
+        ctx.destroy()
+    with pytest.raises(binding.EepError) as ei:     # 2-byte rows cannot be moved 16 B at a time
+        binding.Context(num_ranks=2, slots_per_rank=2, primary_slots=1, num_logical=2,
+                        max_tokens=4, topk=1, hidden=3)
+    assert ei.value.code == binding.ERR_ALIGN
