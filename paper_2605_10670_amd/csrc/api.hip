@@ -112,9 +112,8 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   Tiling g = make_tiling(c->T_max - c->T_max % c->R, c->R);
   c->max_tiles = g.num_tiles > 0 ? g.num_tiles : 1;
   // the map kernel keeps its tables in LDS; refuse shapes that do not fit 64 KiB
-  size_t lds = sizeof(int32_t) * ((size_t)2 * c->E + c->P + (size_t)c->P * kBitmapWords +
-                                  (size_t)2 * kTileTokens * c->k);
-  if (lds > 60 * 1024 || sizeof(int32_t) * ((size_t)2 * c->P + 1) > 60 * 1024) {
+  size_t lds = map_lds_bytes(c->E, c->P, c->R, kTileTokens, c->k);
+  if (lds > 60 * 1024 || sizeof(int32_t) * ((size_t)3 * c->P + 1) > 60 * 1024) {
     delete c;
     return EEP_ERR_INVALID_ARG;
   }

@@ -34,6 +34,13 @@ inline Tiling make_tiling(int T, int R) {
   return g;
 }
 
+// LDS bytes of the map kernel: placement CSR, active mask, live-replica table,
+// per-slot token bitmaps and the tile's router indices / chosen slots.
+inline size_t map_lds_bytes(int E, int P, int R, int tile_tokens, int k) {
+  return sizeof(int32_t) * ((size_t)(E + 1) + P + R + E + P + (size_t)P * kBitmapWords +
+                            (size_t)2 * tile_tokens * k);
+}
+
 inline int dtype_bytes(int dt) { return dt == EEP_F32 ? 4 : dt == EEP_BF16 ? 2 : 1; }
 
 struct PatchChunk {

@@ -7,39 +7,52 @@
 // Sec. 3.2 (validity contract), Sec. 4.1 (contiguous per-expert receive
 // buffers as in prior work).
 //
-// Three launches, all tiny and latency-bound (the step's metadata is < 1 MB):
-//   k_map_count  one workgroup per tile of <= 128 tokens of ONE source rank:
-//                builds the live-replica table in LDS from the placement CSR and
-//                the active mask, maps its pairs, and records for every slot a
-//                bitmap of the tile's tokens that hit it.  popcount of the
-//                bitmap is the tile's count; popcount of the bits below a token
-//                is that pair's stable rank inside the tile.  No atomics on
-//                positions, so the order is deterministic.
-//   k_scan       one workgroup: column sums over tiles, exclusive scan over
-//                slots, per-tile bases, per-rank and per-source-rank tables.
-//   k_position   one workgroup per tile: row = tile base + rank in tile; also
-//                writes the inverse permutation.
+// Two or three launches, all tiny and latency-bound (the step's metadata is
+// < 1 MB), so the design goal is a short chain of dependent memory round trips,
+// not bandwidth.  Every kernel issues all its global loads before its first
+// wait.
+//   k_map_count  one workgroup per tile of <= 128 tokens of ONE source rank.
+//                Placement CSR, active mask and the tile's router indices are
+//                fetched into LDS with independent loads; the live-replica
+//                table is then built from LDS.  For every slot the kernel
+//                records a bitmap of the tile's tokens that hit it: popcount
+//                of the bitmap is the tile's count, popcount of the bits below
+//                a token is that pair's stable rank inside the tile.  No
+//                atomics on positions, so the order is deterministic.
+//   k_scan_position  (<= 64 tiles) one workgroup per tile.  Counts are stored
+//                slot-major ([P][tiles]), so a wavefront scans a slot's tiles
+//                with lane = tile (segmented wave scan); slot totals are then
+//                scanned across the workgroup; row = slot offset + pairs of
+//                earlier tiles + rank in tile.  Each workgroup repeats the
+//                small scan rather than wait for another kernel.
+//   k_scan + k_position  (> 64 tiles) the same scan done once by one
+//                workgroup, then a wide grid computes the rows.
 #include "eep_internal.hpp"
 
 namespace eep {
 
-constexpr int kMapThreads = 256;
-constexpr int kScanThreads = 512;
+constexpr int kMapThreads = 512;
+constexpr int kScanThreads = 1024;
+constexpr int kPosThreads = 256;
 
 // A token can hit a slot at most once: its k logical experts are distinct
 // (repeats are masked) and a slot holds one logical expert.  So one bit per
 // (slot, token of the tile) is enough.
+template <int KC>  // KC = compile-time k (power of two) or 0 for any k
 __global__ __launch_bounds__(kMapThreads) void k_map_count(
     const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ l2p_off,
     const int32_t* __restrict__ l2p_list, const int32_t* __restrict__ active,
     int32_t* __restrict__ slot_of, int32_t* __restrict__ rank_in_tile,
-    int32_t* __restrict__ cnt_tile, int32_t* __restrict__ blk_unc, int32_t* __restrict__ blk_msk,
-    int k, int E, int S, int P, int tokens_per_rank, int tiles_per_rank, int tile_tokens,
-    int policy) {
+    int32_t* __restrict__ cnt_t, int32_t* __restrict__ blk_unc, int32_t* __restrict__ blk_msk,
+    int k_rt, int E, int R, int S, int P, int tokens_per_rank, int tiles_per_rank,
+    int tile_tokens, int num_tiles, int policy) {
+  const int k = KC > 0 ? KC : k_rt;
   extern __shared__ int32_t smem[];
-  int32_t* s_nlive = smem;                       // [E] live replicas of expert e
-  int32_t* s_off = s_nlive + E;                  // [E] start of e's replica list
-  int32_t* s_live = s_off + E;                   // [P] live replicas, compacted per expert
+  int32_t* s_off = smem;                         // [E+1] replica-list starts (CSR)
+  int32_t* s_list = s_off + (E + 1);             // [P] replica lists, canonical order
+  int32_t* s_active = s_list + P;                // [R]
+  int32_t* s_nlive = s_active + R;               // [E] live replicas of expert e
+  int32_t* s_live = s_nlive + E;                 // [P] live replicas, compacted per expert
   uint32_t* s_bm = (uint32_t*)(s_live + P);      // [P][kBitmapWords]
   int32_t* s_idx = (int32_t*)(s_bm + P * kBitmapWords);  // [tile_tokens*k] router indices
   int32_t* s_slot = s_idx + tile_tokens * k;             // [tile_tokens*k] chosen slots
@@ -57,18 +70,23 @@ __global__ __launch_bounds__(kMapThreads) void k_map_count(
   const int npairs = ntok * k;
   const int64_t g0 = (int64_t)t0 * k;
 
+  // every global read of this kernel is issued here, none depends on another
   for (int i = tid; i < npairs; i += kMapThreads) s_idx[i] = topk_idx[g0 + i];
-  for (int e = tid; e < E; e += kMapThreads) {
-    int o = l2p_off[e], o1 = l2p_off[e + 1], n = 0;
-    for (int q = o; q < o1; ++q) {
-      int p = l2p_list[q];
-      if (active[p / S] != 0) s_live[o + n++] = p;  // failed peers are skipped
-    }
-    s_nlive[e] = n;
-    s_off[e] = o;
-  }
+  for (int i = tid; i <= E; i += kMapThreads) s_off[i] = l2p_off[i];
+  for (int i = tid; i < P; i += kMapThreads) s_list[i] = l2p_list[i];
+  for (int i = tid; i < R; i += kMapThreads) s_active[i] = active[i];
   for (int i = tid; i < P * kBitmapWords; i += kMapThreads) s_bm[i] = 0u;
   if (tid < 2) s_drop[tid] = 0;
+  __syncthreads();
+
+  for (int e = tid; e < E; e += kMapThreads) {
+    int o = s_off[e], o1 = s_off[e + 1], n = 0;
+    for (int q = o; q < o1; ++q) {
+      int p = s_list[q];
+      if (s_active[p / S] != 0) s_live[o + n++] = p;  // failed peers are skipped
+    }
+    s_nlive[e] = n;
+  }
   __syncthreads();
 
   int n_unc = 0, n_msk = 0;
@@ -116,8 +134,9 @@ __global__ __launch_bounds__(kMapThreads) void k_map_count(
   }
   for (int p = tid; p < P; p += kMapThreads) {
     int c = 0;
+#pragma unroll
     for (int w = 0; w < kBitmapWords; ++w) c += __popc(s_bm[p * kBitmapWords + w]);
-    cnt_tile[(int64_t)b * P + p] = c;
+    cnt_t[(int64_t)p * num_tiles + b] = c;  // slot-major
   }
   if (tid == 0) {
     blk_unc[b] = s_drop[0];
@@ -125,56 +144,29 @@ __global__ __launch_bounds__(kMapThreads) void k_map_count(
   }
 }
 
-__device__ inline int wave_inclusive_scan(int v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
+// inclusive scan inside aligned groups of `seg` lanes (seg a power of two <= 64)
+__device__ inline int seg_inclusive_scan(int v, int seg) {
+  const int sl = (threadIdx.x & 63) & (seg - 1);
+  for (int d = 1; d < seg; d <<= 1) {
     int o = __shfl_up(v, d, 64);
-    if (lane >= d) v += o;
+    if (sl >= d) v += o;
   }
   return v;
 }
 
-__global__ __launch_bounds__(kScanThreads) void k_scan(
-    const int32_t* __restrict__ cnt_tile, const int32_t* __restrict__ blk_unc,
-    const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
-    int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
-    int32_t* __restrict__ rank_offset, int32_t* __restrict__ cnt_src,
-    int32_t* __restrict__ base_tile, int32_t* __restrict__ status, int num_tiles,
-    int tiles_per_rank, int R, int S, int P) {
-  extern __shared__ int32_t smem[];
-  int32_t* s_count = smem;           // [P]
-  int32_t* s_offset = s_count + P;   // [P+1]
-  __shared__ int32_t s_wave[kScanThreads / 64];
-  __shared__ int32_t s_drop[2];
+// Exclusive scan of s_count[0..P) into s_offset[0..P] by the whole workgroup
+// (NT threads, NT/64 <= 16 wavefronts).  Ends with a barrier.
+template <int NT>
+__device__ inline void block_exclusive_scan(const int32_t* s_count, int32_t* s_offset,
+                                            int32_t* s_wave, int P) {
   const int tid = threadIdx.x;
-  const int n_src = num_tiles > 0 ? R : 0;
-
-  if (tid < 2) s_drop[tid] = 0;
-  // column sums: pairs per slot, and per (source rank, slot)
-  for (int p = tid; p < P; p += kScanThreads) {
-    int total = 0;
-    for (int bs = 0; bs < n_src; ++bs) {
-      int part = 0;
-      for (int sub = 0; sub < tiles_per_rank; ++sub)
-        part += cnt_tile[(int64_t)(bs * tiles_per_rank + sub) * P + p];
-      cnt_src[bs * P + p] = part;
-      total += part;
-    }
-    for (int bs = n_src; bs < R; ++bs) cnt_src[bs * P + p] = 0;
-    s_count[p] = total;
-    count[p] = total;
-  }
-  __syncthreads();
-
-  // exclusive scan over slots: each thread owns a contiguous chunk
-  const int ipt = (P + kScanThreads - 1) / kScanThreads;
+  const int ipt = (P + NT - 1) / NT;
   const int lo = tid * ipt;
   int hi = lo + ipt;
   if (hi > P) hi = P;
   int local = 0;
   for (int p = lo; p < hi; ++p) local += s_count[p];
-  int incl = wave_inclusive_scan(local);
+  int incl = seg_inclusive_scan(local, 64);
   if ((tid & 63) == 63) s_wave[tid >> 6] = incl;
   __syncthreads();
   int wave_base = 0;
@@ -184,93 +176,315 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(
     s_offset[p] = run;
     run += s_count[p];
   }
-  if (tid == kScanThreads - 1) s_offset[P] = wave_base + incl;
-  // dropped-pair totals
-  int du = 0, dm = 0;
-  for (int b = tid; b < num_tiles; b += kScanThreads) {
-    du += blk_unc[b];
-    dm += blk_msk[b];
-  }
-  if (du) atomicAdd(&s_drop[0], du);
-  if (dm) atomicAdd(&s_drop[1], dm);
+  if (tid == NT - 1) s_offset[P] = wave_base + incl;
   __syncthreads();
+}
 
-  for (int p = tid; p <= P; p += kScanThreads) offset[p] = s_offset[p];
-  for (int r = tid; r < R; r += kScanThreads) {
+// Per-step tables every consumer needs, written once by one workgroup.
+template <int NT>
+__device__ inline void write_step_tables(const int32_t* s_count, const int32_t* s_offset,
+                                         int dropped_unc, int dropped_msk, int version,
+                                         int32_t* __restrict__ count, int32_t* __restrict__ offset,
+                                         int32_t* __restrict__ rank_count,
+                                         int32_t* __restrict__ rank_offset,
+                                         int32_t* __restrict__ status, int R, int S, int P) {
+  const int tid = threadIdx.x;
+  for (int p = tid; p <= P; p += NT) {
+    offset[p] = s_offset[p];
+    if (p < P) count[p] = s_count[p];
+  }
+  for (int r = tid; r < R; r += NT) {
     rank_offset[r] = s_offset[r * S];
     rank_count[r] = s_offset[(r + 1) * S] - s_offset[r * S];
   }
   if (tid == 0) {
     rank_offset[R] = s_offset[P];
     status[0] = s_offset[P];
-    status[1] = s_drop[0];
-    status[2] = s_drop[1];
-    status[3] = *tbl_version;
-  }
-  // first row of every (tile, slot): slot offset + pairs of earlier tiles
-  for (int p = tid; p < P; p += kScanThreads) {
-    int acc = s_offset[p];
-    for (int b = 0; b < num_tiles; ++b) {
-      base_tile[(int64_t)b * P + p] = acc;
-      acc += cnt_tile[(int64_t)b * P + p];
-    }
+    status[1] = dropped_unc;
+    status[2] = dropped_msk;
+    status[3] = version;
   }
 }
 
-__global__ __launch_bounds__(kMapThreads) void k_position(
-    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ base_tile,
-    const int32_t* __restrict__ status, int32_t* __restrict__ row_of, int32_t* __restrict__ src_of,
-    int k, int P, int tokens_per_rank, int tiles_per_rank, int tile_tokens) {
+// ---------------------------------------------------------------------------
+// Few tiles (<= 64, the decode regime): scan and position fused.  Every
+// workgroup (one per tile) re-derives what it needs from the [P][tiles] count
+// matrix -- slot totals and the pairs of earlier tiles -- so that the whole
+// kernel has ONE round of global loads, all issued before the first wait.
+// ---------------------------------------------------------------------------
+constexpr int kFusedThreads = 512;
+constexpr int kFusedBatch = 20;   // slots (or slot pairs, ...) in flight per wavefront
+constexpr int kFusedPairs = 4;    // pairs of the tile kept in registers per thread
+
+template <int KC>
+__global__ __launch_bounds__(kFusedThreads) void k_scan_position(
+    const int32_t* __restrict__ cnt_t, const int32_t* __restrict__ blk_unc,
+    const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
+    const int32_t* __restrict__ slot_of, int32_t* __restrict__ row_of,
+    int32_t* __restrict__ src_of, int32_t* __restrict__ count, int32_t* __restrict__ offset,
+    int32_t* __restrict__ rank_count, int32_t* __restrict__ rank_offset,
+    int32_t* __restrict__ cnt_src, int32_t* __restrict__ status, int k_rt, int num_tiles,
+    int tokens_per_rank, int tiles_per_rank, int tile_tokens, int R, int S, int P, int seg) {
+  const int k = KC > 0 ? KC : k_rt;
+  extern __shared__ int32_t smem[];
+  int32_t* s_count = smem;           // [P]   pairs per slot, all tiles
+  int32_t* s_offset = s_count + P;   // [P+1] exclusive scan of s_count
+  int32_t* s_pre = s_offset + P + 1; // [P]   pairs per slot in tiles before this one
+  __shared__ int32_t s_wave[kFusedThreads / 64];
+  __shared__ int32_t s_drop[2];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  constexpr int kWaves = kFusedThreads / 64;
   const int b = blockIdx.x;
   const int src_rank = b / tiles_per_rank;
-  const int sub = b - src_rank * tiles_per_rank;
-  const int t0 = src_rank * tokens_per_rank + sub * tile_tokens;
+  const int sub_tile = b - src_rank * tiles_per_rank;
+  const int t0 = src_rank * tokens_per_rank + sub_tile * tile_tokens;
   int t1 = t0 + tile_tokens;
   const int rank_end = (src_rank + 1) * tokens_per_rank;
   if (t1 > rank_end) t1 = rank_end;
   const int npairs = (t1 > t0 ? t1 - t0 : 0) * k;
   const int g0 = t0 * k;
-  const int N = status[0];
-  const int32_t* base = base_tile + (int64_t)b * P;
-  for (int i = threadIdx.x; i < npairs; i += kMapThreads) {
-    int g = g0 + i;
-    int p = slot_of[g];
-    int row = -1;
-    if (p >= 0) {
-      row = base[p] + row_of[g];  // row_of still holds the rank inside the tile
-      src_of[row] = g;
+
+  // ---- the one round of global loads -------------------------------------
+  int my_slot[kFusedPairs], my_rank[kFusedPairs];
+#pragma unroll
+  for (int u = 0; u < kFusedPairs; ++u) {
+    int i = tid + u * kFusedThreads;
+    my_slot[u] = i < npairs ? slot_of[g0 + i] : -1;
+    my_rank[u] = i < npairs ? row_of[g0 + i] : 0;  // rank inside the tile
+  }
+  int du = 0, dm = 0, version = 0;
+  if (b == 0) {
+    for (int i = tid; i < num_tiles; i += kFusedThreads) {
+      du += blk_unc[i];
+      dm += blk_msk[i];
     }
-    row_of[g] = row;
-    if (g >= N) src_of[g] = -1;  // rows past the last routed pair
+    if (tid == 0) version = *tbl_version;
+  }
+  const int cols = 64 / seg;        // slots per wavefront pass
+  const int sub = lane / seg;       // which of them this lane works on
+  const int sl = lane - sub * seg;  // lane inside the segment = tile index
+  if (tid < 2) s_drop[tid] = 0;
+  for (int c0 = wave * cols; c0 < P; c0 += kWaves * cols * kFusedBatch) {
+    int local[kFusedBatch];
+#pragma unroll
+    for (int u = 0; u < kFusedBatch; ++u) {
+      int p = c0 + u * kWaves * cols + sub;
+      local[u] = (p < P && sl < num_tiles) ? cnt_t[(int64_t)p * num_tiles + sl] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < kFusedBatch; ++u) {
+      int p = c0 + u * kWaves * cols + sub;
+      if (c0 + u * kWaves * cols >= P) break;  // uniform per wavefront
+      int incl = seg_inclusive_scan(local[u], seg);
+      int excl = incl - local[u];
+      int total = __shfl(incl, sub * seg + seg - 1, 64);
+      int before_me = __shfl(excl, sub * seg + b, 64);
+      // pairs of this slot that come from this tile's source rank
+      int first = src_rank * tiles_per_rank;
+      int src_part = __shfl(incl, sub * seg + first + tiles_per_rank - 1, 64) -
+                     __shfl(excl, sub * seg + first, 64);
+      if (p < P && sl == 0) {
+        s_count[p] = total;
+        s_pre[p] = before_me;
+        if (sub_tile == 0) cnt_src[(int64_t)src_rank * P + p] = src_part;
+      }
+    }
+  }
+  __syncthreads();
+  if (du) atomicAdd(&s_drop[0], du);  // zeroed before the barrier, read after the scan's barriers
+  if (dm) atomicAdd(&s_drop[1], dm);
+  block_exclusive_scan<kFusedThreads>(s_count, s_offset, s_wave, P);
+
+  const int N = s_offset[P];
+#pragma unroll
+  for (int u = 0; u < kFusedPairs; ++u) {
+    int i = tid + u * kFusedThreads;
+    if (i < npairs) {
+      int p = my_slot[u];
+      int row = -1;
+      if (p >= 0) {
+        row = s_offset[p] + s_pre[p] + my_rank[u];
+        src_of[row] = g0 + i;
+      }
+      row_of[g0 + i] = row;
+      if (g0 + i >= N) src_of[g0 + i] = -1;  // rows past the last routed pair
+    }
+  }
+  if (b == 0)
+    write_step_tables<kFusedThreads>(s_count, s_offset, s_drop[0], s_drop[1], version, count,
+                                     offset, rank_count, rank_offset, status, R, S, P);
+}
+
+// ---------------------------------------------------------------------------
+// Many tiles (> 64, the prefill regime): one workgroup scans, a wide grid
+// positions.  cnt_t / pre_t are [P][num_tiles]; a slot's tiles are spread over
+// the 64 lanes, each lane owning `per_lane` consecutive tiles.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kScanThreads) void k_scan(
+    const int32_t* __restrict__ cnt_t, const int32_t* __restrict__ blk_unc,
+    const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
+    int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
+    int32_t* __restrict__ rank_offset, int32_t* __restrict__ pre_t, int32_t* __restrict__ status,
+    int num_tiles, int R, int S, int P, int per_lane) {
+  extern __shared__ int32_t smem[];
+  int32_t* s_count = smem;           // [P]
+  int32_t* s_offset = s_count + P;   // [P+1]
+  __shared__ int32_t s_wave[kScanThreads / 64];
+  __shared__ int32_t s_drop[2];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  constexpr int kWaves = kScanThreads / 64;
+  constexpr int kBatch = 8;
+
+  if (tid < 2) s_drop[tid] = 0;
+  int du = 0, dm = 0;
+  for (int b = tid; b < num_tiles; b += kScanThreads) {
+    du += blk_unc[b];
+    dm += blk_msk[b];
+  }
+  const int version = *tbl_version;
+  const int b0 = lane * per_lane;
+  for (int c0 = wave; c0 < P; c0 += kWaves * kBatch) {
+    int local[kBatch];
+    // issue the loads of kBatch slots before any of them is needed
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      int p = c0 + u * kWaves;
+      int acc = 0;
+      if (p < P)
+        for (int i = 0; i < per_lane; ++i)
+          if (b0 + i < num_tiles) acc += cnt_t[(int64_t)p * num_tiles + b0 + i];
+      local[u] = acc;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      int p = c0 + u * kWaves;
+      if (p >= P) break;  // uniform per wavefront
+      int incl = seg_inclusive_scan(local[u], 64);
+      int total = __shfl(incl, 63, 64);
+      int run = incl - local[u];  // pairs of this slot in earlier tiles
+      for (int i = 0; i < per_lane; ++i)
+        if (b0 + i < num_tiles) {
+          pre_t[(int64_t)p * num_tiles + b0 + i] = run;
+          run += cnt_t[(int64_t)p * num_tiles + b0 + i];
+        }
+      if (lane == 0) s_count[p] = total;
+    }
+  }
+  __syncthreads();
+  if (du) atomicAdd(&s_drop[0], du);  // zeroed before the barrier, read after the scan's barriers
+  if (dm) atomicAdd(&s_drop[1], dm);
+  block_exclusive_scan<kScanThreads>(s_count, s_offset, s_wave, P);
+  write_step_tables<kScanThreads>(s_count, s_offset, s_drop[0], s_drop[1], version, count, offset,
+                                  rank_count, rank_offset, status, R, S, P);
+}
+
+template <int KC>
+__global__ __launch_bounds__(kPosThreads) void k_position(
+    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pre_t,
+    const int32_t* __restrict__ offset, const int32_t* __restrict__ status,
+    int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int32_t* __restrict__ cnt_src,
+    int k_rt, int tokens_per_rank, int tiles_per_rank, int tile_tokens, int num_tiles,
+    int total_pairs, int R, int P) {
+  const int k = KC > 0 ? KC : k_rt;
+  const int g = blockIdx.x * kPosThreads + threadIdx.x;
+  // pairs per (source rank, slot): difference of the tile prefixes at the source
+  // rank's first tile and at the next source rank's first tile
+  for (int i = g; i < R * P; i += gridDim.x * kPosThreads) {
+    int bs = i / P;
+    int p = i - bs * P;
+    int first = bs * tiles_per_rank, next = first + tiles_per_rank;
+    int lo_v = pre_t[(int64_t)p * num_tiles + first];
+    int hi_v = next < num_tiles ? pre_t[(int64_t)p * num_tiles + next]
+                                : offset[p + 1] - offset[p];
+    cnt_src[i] = hi_v - lo_v;
+  }
+  if (g >= total_pairs) return;
+  const int t = g / k;
+  const int src_rank = t / tokens_per_rank;
+  const int tile = src_rank * tiles_per_rank + (t - src_rank * tokens_per_rank) / tile_tokens;
+  const int N = status[0];
+  int p = slot_of[g];
+  int row = -1;
+  if (p >= 0) {
+    row = offset[p] + pre_t[(int64_t)p * num_tiles + tile] + row_of[g];  // row_of: rank in tile
+    src_of[row] = g;
+  }
+  row_of[g] = row;
+  if (g >= N) src_of[g] = -1;  // rows past the last routed pair
+}
+
+// T == 0: nothing is routed; publish empty tables.
+__global__ __launch_bounds__(256) void k_empty_step(
+    const int32_t* __restrict__ tbl_version, int32_t* __restrict__ count,
+    int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
+    int32_t* __restrict__ rank_offset, int32_t* __restrict__ cnt_src,
+    int32_t* __restrict__ status, int R, int P) {
+  for (int p = threadIdx.x; p <= P; p += 256) {
+    offset[p] = 0;
+    if (p < P) count[p] = 0;
+  }
+  for (int r = threadIdx.x; r <= R; r += 256) {
+    rank_offset[r] = 0;
+    if (r < R) rank_count[r] = 0;
+  }
+  for (int i = threadIdx.x; i < R * P; i += 256) cnt_src[i] = 0;
+  if (threadIdx.x == 0) {
+    status[0] = status[1] = status[2] = 0;
+    status[3] = *tbl_version;
   }
 }
 
 hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st) {
   Tiling g = make_tiling(T, c->R);
-  if (g.num_tiles > 0) {
-    size_t lds = sizeof(int32_t) * ((size_t)2 * c->E + c->P + (size_t)c->P * kBitmapWords +
-                                    (size_t)2 * g.tile_tokens * c->k);
-    hipLaunchKernelGGL(k_map_count, dim3(g.num_tiles), dim3(kMapThreads), lds, st, topk_idx,
-                       c->l2p_off, c->l2p_list, c->active, c->slot_of, c->row_of, c->cnt_tile,
-                       c->blk_unc, c->blk_msk, c->k, c->E, c->S, c->P, g.tokens_per_rank,
-                       g.tiles_per_rank, g.tile_tokens, c->cfg.policy);
+  const bool k8 = c->k == 8;
+  if (g.num_tiles == 0) {
+    hipLaunchKernelGGL(k_empty_step, dim3(1), dim3(256), 0, st, c->tbl_version, c->count,
+                       c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status, c->R,
+                       c->P);
+    return hipGetLastError();
+  }
+  {
+    size_t lds = map_lds_bytes(c->E, c->P, c->R, g.tile_tokens, c->k);
+    auto kern = k8 ? k_map_count<8> : k_map_count<0>;
+    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kMapThreads), lds, st, topk_idx, c->l2p_off,
+                       c->l2p_list, c->active, c->slot_of, c->row_of, c->cnt_tile, c->blk_unc,
+                       c->blk_msk, c->k, c->E, c->R, c->S, c->P, g.tokens_per_rank,
+                       g.tiles_per_rank, g.tile_tokens, g.num_tiles, c->cfg.policy);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  const bool fused = g.num_tiles <= 64 && g.tile_tokens * c->k <= kFusedThreads * kFusedPairs;
+  if (fused) {
+    int seg = 1;
+    while (seg < g.num_tiles) seg <<= 1;
+    size_t lds = sizeof(int32_t) * ((size_t)3 * c->P + 1);
+    auto kern = k8 ? k_scan_position<8> : k_scan_position<0>;
+    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kFusedThreads), lds, st, c->cnt_tile,
+                       c->blk_unc, c->blk_msk, c->tbl_version, c->slot_of, c->row_of, c->src_of,
+                       c->count, c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
+                       c->k, g.num_tiles, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, c->R,
+                       c->S, c->P, seg);
+    return hipGetLastError();
+  }
+  int per_lane = (g.num_tiles + 63) / 64;
   size_t lds_scan = sizeof(int32_t) * ((size_t)2 * c->P + 1);
   hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), lds_scan, st, c->cnt_tile, c->blk_unc,
                      c->blk_msk, c->tbl_version, c->count, c->offset, c->rank_count,
-                     c->rank_offset, c->cnt_src, c->base_tile, c->status, g.num_tiles,
-                     g.tiles_per_rank, c->R, c->S, c->P);
+                     c->rank_offset, c->base_tile, c->status, g.num_tiles, c->R, c->S, c->P,
+                     per_lane);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (g.num_tiles > 0) {
-    hipLaunchKernelGGL(k_position, dim3(g.num_tiles), dim3(kMapThreads), 0, st, c->slot_of,
-                       c->base_tile, c->status, c->row_of, c->src_of, c->k, c->P,
-                       g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens);
-    e = hipGetLastError();
-  }
-  return e;
+  int total_pairs = T * c->k;
+  auto kern = k8 ? k_position<8> : k_position<0>;
+  hipLaunchKernelGGL(kern, dim3((total_pairs + kPosThreads - 1) / kPosThreads), dim3(kPosThreads),
+                     0, st, c->slot_of, c->base_tile, c->offset, c->status, c->row_of, c->src_of,
+                     c->cnt_src, c->k, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens,
+                     g.num_tiles, total_pairs, c->R, c->P);
+  return hipGetLastError();
 }
 
 }  // namespace eep

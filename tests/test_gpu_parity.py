@@ -104,6 +104,25 @@ def test_decode_shape_ragged_sizes(oracle, T):
     assert got["N"] == T * wl.k
 
 
+@pytest.mark.parametrize("R,T", [(32, 16384), (32, 20576), (3, 600), (1, 77), (64, 64 * 130)])
+def test_many_tiles_and_odd_rank_counts(oracle, R, T):
+    """More than 64 tiles (several tiles per scan lane), ragged tiles inside a
+    source rank, rank counts that are not powers of two, a single rank."""
+    rng = np.random.default_rng(R + T)
+    H, k, sp, sr = 128, 8, 4, 1
+    E = R * sp
+    k = min(k, E)
+    x = synth.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    failed = (R // 2,) if R >= 8 else ()
+    pref = synth.preferred_placement(R, sp, sr)
+    p2l = synth.repaired_placement(pref, failed, R, sp, sr) if failed else pref
+    wl = synth.Workload("tiles", T, H, E, k, R, sp, sr, "bf16", "bf16", "bf16", "identity", failed,
+                        idx, w, x, p2l, synth.active_mask(R, failed))
+    got, _ = run_and_compare(oracle, wl)
+    assert got["N"] == T * k
+
+
 def test_masked_repeated_and_out_of_range_indices(oracle):
     wl = synth.decode(T=256, H=256)
     rng = np.random.default_rng(5)
