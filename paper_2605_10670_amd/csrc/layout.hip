@@ -19,12 +19,13 @@
 //                of the bitmap is the tile's count, popcount of the bits below
 //                a token is that pair's stable rank inside the tile.  No
 //                atomics on positions, so the order is deterministic.
-//   k_scan_position  (<= 64 tiles) one workgroup per tile.  Counts are stored
-//                slot-major ([P][tiles]), so a wavefront scans a slot's tiles
-//                with lane = tile (segmented wave scan); slot totals are then
-//                scanned across the workgroup; row = slot offset + pairs of
-//                earlier tiles + rank in tile.  Each workgroup repeats the
-//                small scan rather than wait for another kernel.
+//   k_scan_position  (<= 64 tiles) one workgroup per tile.  Thread = slot walks
+//                the [tiles][P] count matrix in registers (coalesced, no
+//                cross-lane traffic) for the slot total and the pairs of
+//                earlier tiles; slot totals are then scanned across the
+//                workgroup; row = slot offset + pairs of earlier tiles + rank
+//                in tile.  Each workgroup repeats the small scan rather than
+//                wait for another kernel.
 //   k_scan + k_position  (> 64 tiles) the same scan done once by one
 //                workgroup, then a wide grid computes the rows.
 #include "eep_internal.hpp"
@@ -43,9 +44,9 @@ __global__ __launch_bounds__(kMapThreads) void k_map_count(
     const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ l2p_off,
     const int32_t* __restrict__ l2p_list, const int32_t* __restrict__ active,
     int32_t* __restrict__ slot_of, int32_t* __restrict__ rank_in_tile,
-    int32_t* __restrict__ cnt_t, int32_t* __restrict__ blk_unc, int32_t* __restrict__ blk_msk,
-    int k_rt, int E, int R, int S, int P, int tokens_per_rank, int tiles_per_rank,
-    int tile_tokens, int num_tiles, int policy) {
+    int32_t* __restrict__ cnt_tile, int32_t* __restrict__ blk_unc,
+    int32_t* __restrict__ blk_msk, int k_rt, int E, int R, int S, int P, int tokens_per_rank,
+    int tiles_per_rank, int tile_tokens, int policy) {
   const int k = KC > 0 ? KC : k_rt;
   extern __shared__ int32_t smem[];
   int32_t* s_off = smem;                         // [E+1] replica-list starts (CSR)
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(kMapThreads) void k_map_count(
     int c = 0;
 #pragma unroll
     for (int w = 0; w < kBitmapWords; ++w) c += __popc(s_bm[p * kBitmapWords + w]);
-    cnt_t[(int64_t)p * num_tiles + b] = c;  // slot-major
+    cnt_tile[(int64_t)b * P + p] = c;
   }
   if (tid == 0) {
     blk_unc[b] = s_drop[0];
@@ -208,23 +209,24 @@ __device__ inline void write_step_tables(const int32_t* s_count, const int32_t* 
 
 // ---------------------------------------------------------------------------
 // Few tiles (<= 64, the decode regime): scan and position fused.  Every
-// workgroup (one per tile) re-derives what it needs from the [P][tiles] count
-// matrix -- slot totals and the pairs of earlier tiles -- so that the whole
-// kernel has ONE round of global loads, all issued before the first wait.
+// workgroup (one per tile) re-derives what it needs from the [tiles][P] count
+// matrix -- slot totals and the pairs of earlier tiles -- with thread = slot and
+// the tiles walked in registers, so that the kernel has one round of global
+// loads (two beyond 32 tiles), all issued before the first wait.
 // ---------------------------------------------------------------------------
 constexpr int kFusedThreads = 512;
-constexpr int kFusedBatch = 20;   // slots (or slot pairs, ...) in flight per wavefront
 constexpr int kFusedPairs = 4;    // pairs of the tile kept in registers per thread
+constexpr int kTileBatch = 32;    // count-matrix rows fetched per round
 
 template <int KC>
 __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
-    const int32_t* __restrict__ cnt_t, const int32_t* __restrict__ blk_unc,
+    const int32_t* __restrict__ cnt_tile, const int32_t* __restrict__ blk_unc,
     const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
     const int32_t* __restrict__ slot_of, int32_t* __restrict__ row_of,
     int32_t* __restrict__ src_of, int32_t* __restrict__ count, int32_t* __restrict__ offset,
     int32_t* __restrict__ rank_count, int32_t* __restrict__ rank_offset,
     int32_t* __restrict__ cnt_src, int32_t* __restrict__ status, int k_rt, int num_tiles,
-    int tokens_per_rank, int tiles_per_rank, int tile_tokens, int R, int S, int P, int seg) {
+    int tokens_per_rank, int tiles_per_rank, int tile_tokens, int R, int S, int P) {
   const int k = KC > 0 ? KC : k_rt;
   extern __shared__ int32_t smem[];
   int32_t* s_count = smem;           // [P]   pairs per slot, all tiles
@@ -233,9 +235,6 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
   __shared__ int32_t s_wave[kFusedThreads / 64];
   __shared__ int32_t s_drop[2];
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  constexpr int kWaves = kFusedThreads / 64;
   const int b = blockIdx.x;
   const int src_rank = b / tiles_per_rank;
   const int sub_tile = b - src_rank * tiles_per_rank;
@@ -245,8 +244,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
   if (t1 > rank_end) t1 = rank_end;
   const int npairs = (t1 > t0 ? t1 - t0 : 0) * k;
   const int g0 = t0 * k;
+  const int first = src_rank * tiles_per_rank;  // tiles [first, first + tiles_per_rank) share
+                                                // this tile's source rank
 
-  // ---- the one round of global loads -------------------------------------
   int my_slot[kFusedPairs], my_rank[kFusedPairs];
 #pragma unroll
   for (int u = 0; u < kFusedPairs; ++u) {
@@ -262,35 +262,25 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
     }
     if (tid == 0) version = *tbl_version;
   }
-  const int cols = 64 / seg;        // slots per wavefront pass
-  const int sub = lane / seg;       // which of them this lane works on
-  const int sl = lane - sub * seg;  // lane inside the segment = tile index
   if (tid < 2) s_drop[tid] = 0;
-  for (int c0 = wave * cols; c0 < P; c0 += kWaves * cols * kFusedBatch) {
-    int local[kFusedBatch];
+  for (int p = tid; p < P; p += kFusedThreads) {
+    int total = 0, before = 0, src_part = 0;
+    for (int tb = 0; tb < num_tiles; tb += kTileBatch) {
+      int v[kTileBatch];
 #pragma unroll
-    for (int u = 0; u < kFusedBatch; ++u) {
-      int p = c0 + u * kWaves * cols + sub;
-      local[u] = (p < P && sl < num_tiles) ? cnt_t[(int64_t)p * num_tiles + sl] : 0;
-    }
+      for (int u = 0; u < kTileBatch; ++u)
+        v[u] = tb + u < num_tiles ? cnt_tile[(int64_t)(tb + u) * P + p] : 0;
 #pragma unroll
-    for (int u = 0; u < kFusedBatch; ++u) {
-      int p = c0 + u * kWaves * cols + sub;
-      if (c0 + u * kWaves * cols >= P) break;  // uniform per wavefront
-      int incl = seg_inclusive_scan(local[u], seg);
-      int excl = incl - local[u];
-      int total = __shfl(incl, sub * seg + seg - 1, 64);
-      int before_me = __shfl(excl, sub * seg + b, 64);
-      // pairs of this slot that come from this tile's source rank
-      int first = src_rank * tiles_per_rank;
-      int src_part = __shfl(incl, sub * seg + first + tiles_per_rank - 1, 64) -
-                     __shfl(excl, sub * seg + first, 64);
-      if (p < P && sl == 0) {
-        s_count[p] = total;
-        s_pre[p] = before_me;
-        if (sub_tile == 0) cnt_src[(int64_t)src_rank * P + p] = src_part;
+      for (int u = 0; u < kTileBatch; ++u) {
+        int tile = tb + u;
+        total += v[u];
+        before += tile < b ? v[u] : 0;
+        src_part += (tile >= first && tile < first + tiles_per_rank) ? v[u] : 0;
       }
     }
+    s_count[p] = total;
+    s_pre[p] = before;
+    if (sub_tile == 0) cnt_src[(int64_t)src_rank * P + p] = src_part;
   }
   __syncthreads();
   if (du) atomicAdd(&s_drop[0], du);  // zeroed before the barrier, read after the scan's barriers
@@ -319,25 +309,22 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
 
 // ---------------------------------------------------------------------------
 // Many tiles (> 64, the prefill regime): one workgroup scans, a wide grid
-// positions.  cnt_t / pre_t are [P][num_tiles]; a slot's tiles are spread over
-// the 64 lanes, each lane owning `per_lane` consecutive tiles.
+// positions.  Thread = slot; it walks down the [tiles][P] count matrix keeping a
+// running sum and writes pre_tile[tile][slot] = pairs of the slot in earlier
+// tiles.  Loads are fetched kTileBatch rows at a time.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kScanThreads) void k_scan(
-    const int32_t* __restrict__ cnt_t, const int32_t* __restrict__ blk_unc,
+    const int32_t* __restrict__ cnt_tile, const int32_t* __restrict__ blk_unc,
     const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
     int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
-    int32_t* __restrict__ rank_offset, int32_t* __restrict__ pre_t, int32_t* __restrict__ status,
-    int num_tiles, int R, int S, int P, int per_lane) {
+    int32_t* __restrict__ rank_offset, int32_t* __restrict__ pre_tile,
+    int32_t* __restrict__ status, int num_tiles, int R, int S, int P) {
   extern __shared__ int32_t smem[];
   int32_t* s_count = smem;           // [P]
   int32_t* s_offset = s_count + P;   // [P+1]
   __shared__ int32_t s_wave[kScanThreads / 64];
   __shared__ int32_t s_drop[2];
   const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  constexpr int kWaves = kScanThreads / 64;
-  constexpr int kBatch = 8;
 
   if (tid < 2) s_drop[tid] = 0;
   int du = 0, dm = 0;
@@ -346,33 +333,20 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(
     dm += blk_msk[b];
   }
   const int version = *tbl_version;
-  const int b0 = lane * per_lane;
-  for (int c0 = wave; c0 < P; c0 += kWaves * kBatch) {
-    int local[kBatch];
-    // issue the loads of kBatch slots before any of them is needed
+  for (int p = tid; p < P; p += kScanThreads) {
+    int run = 0;
+    for (int tb = 0; tb < num_tiles; tb += kTileBatch) {
+      int v[kTileBatch];
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      int p = c0 + u * kWaves;
-      int acc = 0;
-      if (p < P)
-        for (int i = 0; i < per_lane; ++i)
-          if (b0 + i < num_tiles) acc += cnt_t[(int64_t)p * num_tiles + b0 + i];
-      local[u] = acc;
-    }
+      for (int u = 0; u < kTileBatch; ++u)
+        v[u] = tb + u < num_tiles ? cnt_tile[(int64_t)(tb + u) * P + p] : 0;
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-      int p = c0 + u * kWaves;
-      if (p >= P) break;  // uniform per wavefront
-      int incl = seg_inclusive_scan(local[u], 64);
-      int total = __shfl(incl, 63, 64);
-      int run = incl - local[u];  // pairs of this slot in earlier tiles
-      for (int i = 0; i < per_lane; ++i)
-        if (b0 + i < num_tiles) {
-          pre_t[(int64_t)p * num_tiles + b0 + i] = run;
-          run += cnt_t[(int64_t)p * num_tiles + b0 + i];
-        }
-      if (lane == 0) s_count[p] = total;
+      for (int u = 0; u < kTileBatch; ++u) {
+        if (tb + u < num_tiles) pre_tile[(int64_t)(tb + u) * P + p] = run;
+        run += v[u];
+      }
     }
+    s_count[p] = run;
   }
   __syncthreads();
   if (du) atomicAdd(&s_drop[0], du);  // zeroed before the barrier, read after the scan's barriers
@@ -384,7 +358,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(
 
 template <int KC>
 __global__ __launch_bounds__(kPosThreads) void k_position(
-    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pre_t,
+    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pre_tile,
     const int32_t* __restrict__ offset, const int32_t* __restrict__ status,
     int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int32_t* __restrict__ cnt_src,
     int k_rt, int tokens_per_rank, int tiles_per_rank, int tile_tokens, int num_tiles,
@@ -397,9 +371,8 @@ __global__ __launch_bounds__(kPosThreads) void k_position(
     int bs = i / P;
     int p = i - bs * P;
     int first = bs * tiles_per_rank, next = first + tiles_per_rank;
-    int lo_v = pre_t[(int64_t)p * num_tiles + first];
-    int hi_v = next < num_tiles ? pre_t[(int64_t)p * num_tiles + next]
-                                : offset[p + 1] - offset[p];
+    int lo_v = pre_tile[(int64_t)first * P + p];
+    int hi_v = next < num_tiles ? pre_tile[(int64_t)next * P + p] : offset[p + 1] - offset[p];
     cnt_src[i] = hi_v - lo_v;
   }
   if (g >= total_pairs) return;
@@ -410,7 +383,7 @@ __global__ __launch_bounds__(kPosThreads) void k_position(
   int p = slot_of[g];
   int row = -1;
   if (p >= 0) {
-    row = offset[p] + pre_t[(int64_t)p * num_tiles + tile] + row_of[g];  // row_of: rank in tile
+    row = offset[p] + pre_tile[(int64_t)tile * P + p] + row_of[g];  // row_of: rank in tile
     src_of[row] = g;
   }
   row_of[g] = row;
@@ -453,29 +426,25 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
     hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kMapThreads), lds, st, topk_idx, c->l2p_off,
                        c->l2p_list, c->active, c->slot_of, c->row_of, c->cnt_tile, c->blk_unc,
                        c->blk_msk, c->k, c->E, c->R, c->S, c->P, g.tokens_per_rank,
-                       g.tiles_per_rank, g.tile_tokens, g.num_tiles, c->cfg.policy);
+                       g.tiles_per_rank, g.tile_tokens, c->cfg.policy);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   const bool fused = g.num_tiles <= 64 && g.tile_tokens * c->k <= kFusedThreads * kFusedPairs;
   if (fused) {
-    int seg = 1;
-    while (seg < g.num_tiles) seg <<= 1;
     size_t lds = sizeof(int32_t) * ((size_t)3 * c->P + 1);
     auto kern = k8 ? k_scan_position<8> : k_scan_position<0>;
     hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kFusedThreads), lds, st, c->cnt_tile,
                        c->blk_unc, c->blk_msk, c->tbl_version, c->slot_of, c->row_of, c->src_of,
                        c->count, c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
                        c->k, g.num_tiles, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, c->R,
-                       c->S, c->P, seg);
+                       c->S, c->P);
     return hipGetLastError();
   }
-  int per_lane = (g.num_tiles + 63) / 64;
   size_t lds_scan = sizeof(int32_t) * ((size_t)2 * c->P + 1);
   hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), lds_scan, st, c->cnt_tile, c->blk_unc,
                      c->blk_msk, c->tbl_version, c->count, c->offset, c->rank_count,
-                     c->rank_offset, c->base_tile, c->status, g.num_tiles, c->R, c->S, c->P,
-                     per_lane);
+                     c->rank_offset, c->base_tile, c->status, g.num_tiles, c->R, c->S, c->P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   int total_pairs = T * c->k;
