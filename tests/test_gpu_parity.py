@@ -165,6 +165,50 @@ def test_prefill_fp8_reduced(oracle):
     assert got["rank_count"][7] == 0 and got["rank_count"][20] == 0
 
 
+def test_prefill_fp8_full_size_sampled(oracle):
+    """Prefill shape at full size (T=16384, fp8 payload + scales, two failed
+    ranks).  Layout compared in full; moved rows checked in full against a torch
+    gather (a library routine for the same permutation); stub and combine
+    compared with the oracle on 256 sampled tokens."""
+    wl = synth.prefill_fp8()
+    T, k, H = wl.T, wl.k, wl.H
+    ctx = gu.make_context(wl)
+    try:
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        dev = gu.DeviceStep(ctx, wl)
+        dev.step()
+        dev.sync()
+        lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim, 0)
+        got = ctx.read_layout(T)
+        gu.assert_layout_equal(got, lay, T, k)
+        N = got["N"]
+        assert N == T * k and got["rank_count"][7] == 0 and got["rank_count"][20] == 0
+        src_tok = torch.from_numpy(lay["src_of"][:N] // k).cuda().long()
+        assert torch.equal(dev.recv[:N], dev.x.index_select(0, src_tok)), "packed fp8 rows"
+        assert torch.equal(dev.recv_scale[:N].view(torch.int32),
+                           dev.x_scale.index_select(0, src_tok).view(torch.int32)), "scale rows"
+        del src_tok
+        # sampled tokens: compact sub-problem for the oracle
+        rng = np.random.default_rng(8)
+        toks = np.sort(rng.choice(T, 256, replace=False))
+        rows = lay["row_of"][toks]                                    # [256, k], all routed
+        compact = np.arange(rows.size, dtype=np.int32).reshape(rows.shape)
+        recv_c = oracle.pack(wl.x[toks], compact)
+        scale_c = oracle.pack(wl.x_scale[toks], compact)
+        y_c = oracle.stub_dequant(recv_c, scale_c, rows.size, 128)
+        rows_dev = torch.from_numpy(rows.ravel()).cuda().long()
+        assert np.array_equal(dev.recv.index_select(0, rows_dev).cpu().numpy(), recv_c)
+        y_got = gu.to_host(dev.y.index_select(0, rows_dev), np.uint16)
+        assert np.array_equal(y_got, y_c), "dequantised rows"
+        out64 = oracle.combine(y_c, oracle.BF16, wl.topk_w[toks], compact)
+        chain = oracle.f32_to_bf16(oracle.combine_chain32(y_c, oracle.BF16, wl.topk_w[toks], compact))
+        out_got = gu.to_host(dev.out.index_select(0, torch.from_numpy(toks).cuda().long()), np.uint16)
+        gu.check_combine(out_got, "bf16", out64)
+        assert np.array_equal(out_got, chain)
+    finally:
+        ctx.destroy()
+
+
 def test_decode_full_size(oracle):
     """DeepSeek-V3 decode shape at full size, every output compared."""
     wl = synth.decode()
