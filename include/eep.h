@@ -190,6 +190,12 @@ typedef enum {
  * array into host memory.  n beyond the array's allocated size is an error. */
 int eep_read_view(eep_ctx* ctx, int32_t field, int32_t* host_dst, int64_t n, void* stream);
 
+/* Measurement helper: a plain copy kernel (dst[i] = src[i], 16-byte vectors,
+ * bytes a multiple of 16, both device pointers 16-byte aligned).  It moves
+ * exactly `bytes` in and `bytes` out, which makes it the yardstick that
+ * hardware HBM counters are scaled by when a profile is turned into bytes. */
+int eep_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
+
 const char* eep_strerror(int code);
 /* hipError_t of the last failed HIP call made for this context (0 if none). */
 int eep_last_hip_error(eep_ctx* ctx);

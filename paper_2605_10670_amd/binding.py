@@ -63,6 +63,7 @@ def load():
         "eep_get_view": [vp, ctypes.POINTER(_View)],
         "eep_read_view": [vp, i32, vp, i64, vp],
         "eep_last_hip_error": [vp],
+        "eep_calibration_copy": [vp, vp, i64, vp],
         "eep_graph_begin": [vp, vp],
         "eep_graph_end": [vp, vp, ctypes.POINTER(vp)],
         "eep_graph_launch": [vp, vp],
@@ -106,6 +107,12 @@ def _check(code, what, ctx=None):
         if code == ERR_HIP and ctx is not None:
             err.args = (err.args[0] + f" [hipError {load().eep_last_hip_error(ctx)}]",)
         raise err
+
+
+def calibration_copy(dst, src, nbytes, stream=None):
+    """Plain copy kernel of known size (yardstick for HBM counters)."""
+    _check(load().eep_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)),
+           "eep_calibration_copy")
 
 
 class Graph:
