@@ -55,8 +55,17 @@ def time_events(stream, fn, reps):
 
 
 def cpu_baseline(wl, bytes_total, budget_s=20.0):
-    """The oracle as it stands (single thread) on the same workload."""
+    """The oracle as it stands (single thread) on the same workload: the same
+    three calls as the GPU step (layout, pack, combine); y comes from outside."""
     import oracle
+    ydt = oracle.BF16 if wl.y_dtype == "bf16" else oracle.F32
+    lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim,
+                             oracle.SPREAD)
+    if wl.stub == "identity":
+        y = None
+    else:  # expert stand-in output, prepared outside the timed region like on the GPU
+        import numpy as np
+        y = np.zeros((wl.T * wl.k, wl.H), np.uint16 if wl.y_dtype == "bf16" else np.float32)
     times = []
     t_all = time.perf_counter()
     while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < 10):
@@ -64,7 +73,9 @@ def cpu_baseline(wl, bytes_total, budget_s=20.0):
         lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim,
                                  oracle.SPREAD)
         recv = oracle.pack(wl.x, lay["row_of"])
-        oracle.combine(recv, oracle.BF16, wl.topk_w, lay["row_of"])
+        if wl.x_scale is not None:
+            oracle.pack(wl.x_scale, lay["row_of"])
+        oracle.combine(recv if y is None else y, ydt, wl.topk_w, lay["row_of"])
         times.append(time.perf_counter() - t0)
         if time.perf_counter() - t_all > budget_s:
             break
@@ -74,6 +85,18 @@ def cpu_baseline(wl, bytes_total, budget_s=20.0):
             "sample": f"{len(times)} full {wl.name} steps (T={wl.T}), median"}
 
 
+WORKLOADS = {
+    "decode": ("dsv3-decode: T=4096 (32 ranks x 128), H=7168 bf16, E=256, top-8, 8+1 slots/rank, "
+               "all live, identity expert"),
+    "decode_failed_zipf": ("dsv3-decode, rank 13 failed and remapped to redundant slots, "
+                           "Zipf(1.2)-skewed logits: T=4096, H=7168 bf16, E=256, top-8"),
+    "prefill_fp8": ("dsv3-prefill: T=16384, H=7168 fp8 e4m3 + fp32 scale/128 dispatch, bf16 combine, "
+                    "E=256, top-8, ranks 7 and 20 failed"),
+    "churn": "qwen3-moe-like: T=2048, H=4096 bf16, E=128, top-8, R=16, 8+1 slots/rank, all live",
+}
+BYTES_OF = {"f32": 4, "bf16": 2, "fp8": 1}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -81,6 +104,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="replay a captured hipGraph of the step (default) or launch eagerly")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="decode",
+                    help="decode (default) is the configuration the headline metric is quoted on")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--calib", action="store_true",
                     help="first launch 5 plain copy kernels of 512 MiB (k_calibration_copy), the "
@@ -90,33 +115,57 @@ def main():
         sys.exit("bench.py: this build runs on one GPU only (virtual EP ranks share one HBM); "
                  "use --gpus 1")
 
+    import numpy as np
     import torch
     from paper_2605_10670_amd import binding, synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.calib:
-        a = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        for _ in range(5):
-            binding.calibration_copy(b, a, a.numel())
-        torch.cuda.synchronize()
-        del a, b
-    wl = synth.decode()
+    stream = torch.cuda.Stream()
+
+    # plain-copy ceiling of this GPU (and, with --calib, the counters' yardstick)
+    a = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    copy = lambda: binding.calibration_copy(b, a, a.numel(), stream)
+    for _ in range(5 if args.calib else 2):
+        copy()
+    stream.synchronize()
+    copy_gbs = 2 * a.numel() / (time_events(stream, copy, 10) * 1e-3) / 1e9
+    del a, b
+
+    if args.workload == "decode":
+        wl = synth.decode()
+    elif args.workload == "decode_failed_zipf":
+        wl = synth.decode_failed_zipf()
+    elif args.workload == "prefill_fp8":
+        wl = synth.prefill_fp8()
+    else:
+        wl = synth.churn_inputs(1)[0]
+        wl.stub = "identity"
     T, k, H = wl.T, wl.k, wl.H
-    nbytes = algorithmic_bytes(T, k, H, 2, 2, 2)
+    scale_row = (H // 128) * 4 if wl.x_scale is not None else 0
+    nbytes = algorithmic_bytes(T, k, H, BYTES_OF[wl.x_dtype], BYTES_OF[wl.y_dtype],
+                               BYTES_OF[wl.out_dtype], scale_row)
 
     ctx = binding.Context(num_ranks=wl.R, slots_per_rank=wl.S, primary_slots=wl.S_prim,
-                          num_logical=wl.E, max_tokens=T, topk=k, hidden=H, x_dtype="bf16",
-                          y_dtype="bf16", out_dtype="bf16")
-    stream = torch.cuda.Stream()
-    import numpy as np
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    idx, w = dev(wl.topk_idx), dev(wl.topk_w)
-    x = dev(wl.x.view(np.int16))
-    recv = torch.empty((T * k, H), dtype=torch.int16, device="cuda")
-    out = torch.empty((T, H), dtype=torch.int16, device="cuda")
+                          num_logical=wl.E, max_tokens=T, topk=k, hidden=H, x_dtype=wl.x_dtype,
+                          y_dtype=wl.y_dtype, out_dtype=wl.out_dtype)
+
+    def dev(arr):
+        arr = np.ascontiguousarray(arr)
+        return torch.from_numpy(arr.view(np.int16) if arr.dtype == np.uint16 else arr).cuda()
+
+    tdt = {"f32": torch.float32, "bf16": torch.int16, "fp8": torch.uint8}
+    idx, w, x = dev(wl.topk_idx), dev(wl.topk_w), dev(wl.x)
+    x_scale = dev(wl.x_scale) if wl.x_scale is not None else None
+    recv = torch.empty((T * k, H), dtype=tdt[wl.x_dtype], device="cuda")
+    recv_scale = (torch.empty((T * k, H // 128), dtype=torch.float32, device="cuda")
+                  if x_scale is not None else None)
+    # identity expert: y aliases the receive buffer; otherwise the stand-in fills y once, untimed
+    y = recv if wl.stub == "identity" else torch.empty((T * k, H), dtype=tdt[wl.y_dtype],
+                                                       device="cuda")
+    out = torch.empty((T, H), dtype=tdt[wl.out_dtype], device="cuda")
     torch.cuda.synchronize()
     ctx.update_placement(wl.p2l, stream)
     ctx.set_membership(wl.active, stream)
@@ -125,17 +174,21 @@ def main():
         ctx.dispatch_layout(idx, T, stream)
 
     def dispatch():
-        ctx.dispatch(x, recv, T, stream=stream)
+        ctx.dispatch(x, recv, T, x_scale, recv_scale, stream)
 
     def combine():
-        ctx.combine(recv, w, out, T, stream=stream)   # identity expert: y aliases recv
+        ctx.combine(y, w, out, T, stream=stream)
 
     def step():
         layout()
         dispatch()
         combine()
 
-    step()
+    layout()
+    dispatch()
+    if wl.stub != "identity":
+        ctx.expert_stub(wl.stub, recv, y, T, recv_scale=recv_scale, stream=stream)
+    combine()
     stream.synchronize()
     graph = None
     if args.mode == "graph":
@@ -180,23 +233,25 @@ def main():
         gbs = nbytes[stage] / (stage_ms[stage] * 1e-3) / 1e9
         kernels[kname] = {"avg_launch_us": stage_ms[stage] * 1e3,
                           "algorithmic_bytes_per_launch": nbytes[stage], "achieved": gbs,
-                          "frac": gbs / HBM_PEAK_GBS, "traffic": HBM_TRAFFIC_BYTES.get(kname)}
+                          "frac": gbs / HBM_PEAK_GBS,
+                          "traffic": HBM_TRAFFIC_BYTES.get(kname) if args.workload == "decode"
+                          else None}
     dom = max(kernels, key=lambda n: kernels[n]["avg_launch_us"])
     result = {
         "metric": "dispatch+combine achieved HBM GB/s (algorithmic bytes / step time), "
-                  "DSV3 decode shape",
+                  + ("DSV3 decode shape" if args.workload == "decode" else args.workload),
         "value": nbytes["total"] / (ms * 1e-3) / 1e9,
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "us_per_step": ms * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "dsv3-decode: T=4096 (32 ranks x 128), H=7168 bf16, E=256, top-8, "
-                               "8+1 slots/rank, all live, identity expert",
-                   "mode": args.mode, "step": "dispatch_layout + dispatch + combine",
+        "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "u8"}[wl.x_dtype], "data": "synthetic",
+        "config": {"workload": WORKLOADS[args.workload], "mode": args.mode, "step": "dispatch_layout + dispatch + combine",
                    "algorithmic_bytes_per_step": nbytes["total"]},
         "frac_of_hbm_peak": nbytes["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "wall_ms_per_step": wall_ms,
+        "copy_ceiling_gbs": copy_gbs,
+        "frac_of_copy_ceiling": nbytes["total"] / (ms * 1e-3) / 1e9 / copy_gbs,
         "stages_us": {n: v * 1e3 for n, v in stage_ms.items()},
         "eager_us_per_step": other_ms * 1e3,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved"],
