@@ -159,6 +159,28 @@ def test_dtype_and_topk_matrix(oracle, dtypes, k):
     assert got["rank_count"][4] == 0
 
 
+@pytest.mark.parametrize("shape", [
+    dict(R=128, sp=2, sr=1, k=4, T=128 * 16, H=256, xd="bf16"),    # P=384 slots, many ranks
+    dict(R=8, sp=8, sr=2, k=32, T=8 * 128, H=128, xd="bf16"),      # k=32: tile pairs > fused limit
+    dict(R=4, sp=4, sr=1, k=3, T=4 * 50, H=8192, xd="bf16"),       # 16 KiB rows: two pack passes
+    dict(R=4, sp=4, sr=1, k=5, T=4 * 7, H=5000, xd="f32"),         # 20000-byte fp32 rows, ragged parts
+    dict(R=2, sp=1, sr=3, k=2, T=2 * 300, H=8, xd="bf16"),         # 16-byte rows, more replicas than experts
+])
+def test_wide_and_odd_shapes(oracle, shape):
+    R, sp, sr, k, T, H, xd = (shape[n] for n in ("R", "sp", "sr", "k", "T", "H", "xd"))
+    rng = np.random.default_rng(T + H)
+    E = R * sp
+    x32 = rng.standard_normal((T, H), dtype=np.float32)
+    x = x32 if xd == "f32" else synth.f32_to_bf16_bits(x32)
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), min(k, E))
+    k = idx.shape[1]
+    p2l = synth.preferred_placement(R, sp, sr)
+    wl = synth.Workload("wide", T, H, E, k, R, sp, sr, xd, xd, xd, "scale", (), idx, w, x, p2l,
+                        synth.active_mask(R), expert_scale=(0.5 + rng.random(E)).astype(np.float32))
+    got, _ = run_and_compare(oracle, wl)
+    assert got["N"] == T * k
+
+
 def test_prefill_fp8_reduced(oracle):
     wl = synth.prefill_fp8(T=1024, H=1024)
     got, _ = run_and_compare(oracle, wl)
