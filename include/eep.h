@@ -200,6 +200,49 @@ const char* eep_strerror(int code);
 /* hipError_t of the last failed HIP call made for this context (0 if none). */
 int eep_last_hip_error(eep_ctx* ctx);
 
+/* ---- host-only helpers: touch no GPU; the entry points above run the same
+ * code.  Exposed so that the host logic can be checked on a CPU-only machine. */
+
+/* All physical locations of each logical expert (Sec. 5.1) as CSR over host
+ * arrays: l2p_off[E+1], l2p_list[P] (replicas in canonical order, unused tail
+ * -1).  P must be a multiple of S. */
+int eep_host_replica_lists(int32_t P, int32_t E, int32_t S, int32_t S_prim,
+                           const int32_t* phys_to_logical, int32_t* l2p_off, int32_t* l2p_list);
+/* Number (>= 0) of logical experts with no replica on an active rank: validity
+ * condition 2 of Sec. 3.2 holds iff it is 0.  Negative = eep_status. */
+int eep_host_uncovered_experts(int32_t P, int32_t E, int32_t S, const int32_t* phys_to_logical,
+                               const int32_t* active);
+/* How eep_dispatch_layout tiles T tokens of R source ranks:
+ * out = {tokens per rank, tiles per rank, tokens per tile (<= 128), tiles}. */
+int eep_host_tiling(int32_t T, int32_t R, int32_t out[4]);
+
+/* Placement repair after a membership change (Sec. 3.5, Sec. 5.1; worked
+ * example: Fig. 5, middle panel).  Host only.  Input: what every slot holds now
+ * (cur_phys_to_logical[P], -1 = empty; slots of failed ranks included), the
+ * active mask, and optionally a non-negative load per logical expert (NULL =
+ * uniform).  Output: new_phys_to_logical[P] covering every logical expert on
+ * live ranks (input for eep_update_placement), and for every slot where its
+ * weights come from -- the paper's three-case source hierarchy:
+ *   EEP_SRC_LOCAL  the slot keeps the expert it already holds (local reuse);
+ *   EEP_SRC_PEER   copy from source_slot[p], a live slot holding the expert now
+ *                  (GPU-to-GPU relocation);
+ *   EEP_SRC_DRAM   no live copy existed: reload from the DRAM backup;
+ *   EEP_SRC_NONE   empty slot or slot of a failed rank (left as it was).
+ * The paper does not give its balancer's algorithm; this one is a deterministic
+ * greedy rule: first cover experts with no live copy (hottest first; free slot
+ * on the least-loaded live rank, else evict the cheapest replica that leaves
+ * another live copy, redundant slots first), then use remaining free slots to
+ * re-create lost replicas from surviving copies.
+ * summary = {local, peer, dram, experts left uncovered}.  Returns EEP_OK, or
+ * EEP_ERR_COVERAGE if some expert could not be placed (fewer live slots than
+ * logical experts); outputs are filled in both cases. */
+typedef enum { EEP_SRC_NONE = -1, EEP_SRC_LOCAL = 0, EEP_SRC_PEER = 1, EEP_SRC_DRAM = 2 }
+    eep_repair_source;
+int eep_plan_repair(int32_t R, int32_t S, int32_t S_prim, int32_t E,
+                    const int32_t* cur_phys_to_logical, const int32_t* active, const float* load,
+                    int32_t* new_phys_to_logical, int32_t* source_kind, int32_t* source_slot,
+                    int32_t summary[4]);
+
 /* ---- hipGraph helper (Sec. 2.3, Fig. 4: capture once, replay, patch table
  * contents only) ------------------------------------------------------------
  * eep_graph_begin puts `stream` (not the default stream) into capture mode;

@@ -64,6 +64,10 @@ def load():
         "eep_read_view": [vp, i32, vp, i64, vp],
         "eep_last_hip_error": [vp],
         "eep_calibration_copy": [vp, vp, i64, vp],
+        "eep_host_replica_lists": [i32, i32, i32, i32, vp, vp, vp],
+        "eep_host_uncovered_experts": [i32, i32, i32, vp, vp],
+        "eep_host_tiling": [i32, i32, vp],
+        "eep_plan_repair": [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp],
         "eep_graph_begin": [vp, vp],
         "eep_graph_end": [vp, vp, ctypes.POINTER(vp)],
         "eep_graph_launch": [vp, vp],
@@ -113,6 +117,57 @@ def calibration_copy(dst, src, nbytes, stream=None):
     """Plain copy kernel of known size (yardstick for HBM counters)."""
     _check(load().eep_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)),
            "eep_calibration_copy")
+
+
+def host_replica_lists(p2l, E, S, S_prim):
+    """CSR of every logical expert's replicas (host only) -> (l2p_off, l2p_list)."""
+    p2l = np.ascontiguousarray(p2l, np.int32)
+    off, lst = np.empty(E + 1, np.int32), np.empty(p2l.size, np.int32)
+    _check(load().eep_host_replica_lists(p2l.size, E, S, S_prim, p2l.ctypes.data, off.ctypes.data,
+                                         lst.ctypes.data), "eep_host_replica_lists")
+    return off, lst
+
+
+def host_uncovered_experts(p2l, active, E, S):
+    p2l = np.ascontiguousarray(p2l, np.int32)
+    active = np.ascontiguousarray(active, np.int32)
+    n = load().eep_host_uncovered_experts(p2l.size, E, S, p2l.ctypes.data, active.ctypes.data)
+    if n < 0:
+        _check(n, "eep_host_uncovered_experts")
+    return n
+
+
+def host_tiling(T, R):
+    out = np.empty(4, np.int32)
+    _check(load().eep_host_tiling(T, R, out.ctypes.data), "eep_host_tiling")
+    return dict(tokens_per_rank=int(out[0]), tiles_per_rank=int(out[1]), tile_tokens=int(out[2]),
+                num_tiles=int(out[3]))
+
+
+SRC_NONE, SRC_LOCAL, SRC_PEER, SRC_DRAM = -1, 0, 1, 2
+
+
+def plan_repair(cur_p2l, active, R, S, S_prim, E, load=None):
+    """Repaired placement + source of every slot's weights (host only).
+    Returns dict(p2l, kind, src_slot, local, peer, dram, unplaced)."""
+    cur = np.ascontiguousarray(cur_p2l, np.int32)
+    act = np.ascontiguousarray(active, np.int32)
+    if cur.size != R * S or act.size != R:
+        raise ValueError("cur_p2l must have R*S entries and active R")
+    ld = None if load is None else np.ascontiguousarray(load, np.float32)
+    new, kind, src = (np.empty(R * S, np.int32) for _ in range(3))
+    summary = np.zeros(4, np.int32)
+    rc = load_lib_plan(R, S, S_prim, E, cur, act, ld, new, kind, src, summary)
+    if rc not in (OK, ERR_COVERAGE):
+        _check(rc, "eep_plan_repair")
+    return dict(p2l=new, kind=kind, src_slot=src, local=int(summary[0]), peer=int(summary[1]),
+                dram=int(summary[2]), unplaced=int(summary[3]))
+
+
+def load_lib_plan(R, S, S_prim, E, cur, act, ld, new, kind, src, summary):
+    return load().eep_plan_repair(R, S, S_prim, E, cur.ctypes.data, act.ctypes.data,
+                                  None if ld is None else ld.ctypes.data, new.ctypes.data,
+                                  kind.ctypes.data, src.ctypes.data, summary.ctypes.data)
 
 
 class Graph:

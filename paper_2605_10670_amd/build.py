@@ -6,7 +6,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libeep.so")
-SOURCES = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
+SOURCES = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")) +
+                 glob.glob(os.path.join(HERE, "csrc", "*.cpp")))
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

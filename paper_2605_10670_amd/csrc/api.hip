@@ -15,34 +15,6 @@ int fail_hip(eep_ctx* c, hipError_t e) {
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-// Number of logical experts without a replica on an active rank (validity
-// condition 2 of Sec. 3.2), from host copies of the tables.
-int uncovered_experts(const eep_ctx* c, const int32_t* p2l, const int32_t* active) {
-  std::vector<char> live(c->E, 0);
-  for (int p = 0; p < c->P; ++p)
-    if (p2l[p] >= 0 && active[p / c->S] != 0) live[p2l[p]] = 1;
-  int missing = 0;
-  for (int e = 0; e < c->E; ++e) missing += !live[e];
-  return missing;
-}
-
-// Replica lists per logical expert in canonical order: primary slots first,
-// then redundant ones, each by ascending slot id.
-void build_csr(const eep_ctx* c, const int32_t* p2l, std::vector<int32_t>& off,
-               std::vector<int32_t>& list) {
-  off.assign(c->E + 1, 0);
-  list.assign(c->P, -1);
-  for (int p = 0; p < c->P; ++p)
-    if (p2l[p] >= 0) off[p2l[p] + 1]++;
-  for (int e = 0; e < c->E; ++e) off[e + 1] += off[e];
-  std::vector<int32_t> cur(off.begin(), off.end() - 1);
-  for (int pass = 0; pass < 2; ++pass)
-    for (int p = 0; p < c->P; ++p) {
-      bool redundant = (p % c->S) >= c->S_prim;
-      if (p2l[p] >= 0 && redundant == (pass == 1)) list[cur[p2l[p]]++] = p;
-    }
-}
-
 }  // namespace
 
 extern "C" {
@@ -191,7 +163,7 @@ int eep_set_membership(eep_ctx* c, const int32_t* active_host, void* stream) {
   if (!c || !active_host) return EEP_ERR_INVALID_ARG;
   std::vector<int32_t> a(c->R);
   for (int r = 0; r < c->R; ++r) a[r] = active_host[r] != 0 ? 1 : 0;
-  if (c->cfg.strict_coverage && uncovered_experts(c, c->h_p2l.data(), a.data()) > 0)
+  if (c->cfg.strict_coverage && host_uncovered_experts(c->P, c->E, c->S, c->h_p2l.data(), a.data()) > 0)
     return EEP_ERR_COVERAGE;
   hipError_t e = launch_patch(c->active, a.data(), c->R, c->tbl_version, c->version + 1,
                               (hipStream_t)stream);
@@ -205,10 +177,10 @@ int eep_update_placement(eep_ctx* c, const int32_t* p2l_host, void* stream) {
   if (!c || !p2l_host) return EEP_ERR_INVALID_ARG;
   for (int p = 0; p < c->P; ++p)
     if (p2l_host[p] < -1 || p2l_host[p] >= c->E) return EEP_ERR_INVALID_ARG;
-  if (c->cfg.strict_coverage && uncovered_experts(c, p2l_host, c->h_active.data()) > 0)
+  if (c->cfg.strict_coverage && host_uncovered_experts(c->P, c->E, c->S, p2l_host, c->h_active.data()) > 0)
     return EEP_ERR_COVERAGE;
-  std::vector<int32_t> off, list;
-  build_csr(c, p2l_host, off, list);
+  std::vector<int32_t> off(c->E + 1), list(c->P);
+  host_replica_lists(c->P, c->E, c->S, c->S_prim, p2l_host, off.data(), list.data());
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_patch(c->p2l, p2l_host, c->P, nullptr, 0, st);
   if (e == hipSuccess) e = launch_patch(c->l2p_off, off.data(), c->E + 1, nullptr, 0, st);

@@ -74,6 +74,10 @@ struct eep_ctx {
 
 namespace eep {
 
+// host_logic.cpp (no GPU touched)
+int host_uncovered_experts(int P, int E, int S, const int32_t* p2l, const int32_t* active);
+void host_replica_lists(int P, int E, int S, int S_prim, const int32_t* p2l, int32_t* l2p_off,
+                        int32_t* l2p_list);
 // layout.hip
 hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st);
 // data.hip

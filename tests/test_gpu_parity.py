@@ -250,6 +250,45 @@ def test_decode_failed_rank_zipf_full_size(oracle):
     assert all(p % S == S - 1 for p in hot)        # hottest slots are redundant replicas
 
 
+def test_failure_then_planned_repair_then_rejoin(oracle):
+    """The paper's sequence (Fig. 5, Fig. 6) on the decode shape: healthy step;
+    ranks 3 and 17 fail; the planner repairs the placement from the observed
+    per-expert load; tables are patched (placement, then mask); degraded step;
+    ranks rejoin (mask, then preferred placement); healthy step again.  Every
+    step must match the oracle under the tables in force."""
+    wl = synth.decode(T=1024, H=512)
+    failed = (3, 17)
+    ctx = gu.make_context(wl)
+    try:
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        dev = gu.DeviceStep(ctx, wl)
+
+        def step_and_check(p2l, active):
+            dev.step()
+            dev.sync()
+            ref = oracle_step(oracle, wl, 0, p2l, active)
+            got = ctx.read_layout(wl.T)
+            gu.assert_layout_equal(got, ref["lay"], wl.T, wl.k)
+            out = gu.to_host(dev.out, np.uint16)
+            assert np.array_equal(out, ref["chain_bits"])
+            return got
+
+        got = step_and_check(wl.p2l, wl.active)
+        load = np.bincount(wl.topk_idx.ravel(), minlength=wl.E).astype(np.float32)
+        dead = synth.active_mask(wl.R, failed)
+        plan = binding.plan_repair(wl.p2l, dead, wl.R, wl.S, wl.S_prim, wl.E, load)
+        assert plan["unplaced"] == 0 and plan["dram"] + plan["peer"] > 0
+        ctx.update_placement(plan["p2l"])
+        ctx.set_membership(dead)
+        got = step_and_check(plan["p2l"], dead)
+        assert got["rank_count"][list(failed)].sum() == 0 and got["N"] == wl.T * wl.k
+        ctx.set_membership(wl.active)
+        ctx.update_placement(wl.p2l)
+        step_and_check(wl.p2l, wl.active)
+    finally:
+        ctx.destroy()
+
+
 def test_call_order_and_argument_errors():
     wl = synth.decode(T=64, H=256)
     ctx = gu.make_context(wl)

@@ -28,6 +28,8 @@ def parse_fig5():
             panels.append(cur)
         elif tok[0] == "active":
             cur["active"] = [int(v) for v in tok[1:]]
+        elif tok[0] == "source":
+            cur.setdefault("sources", []).append(tok[1:])
         elif tok[0] == "route":
             cur["routes"][int(tok[1][1:])] = int(tok[2][1:])
         elif tok[0][0] == "R":
