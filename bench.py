@@ -106,6 +106,9 @@ def main():
                     help="replay a captured hipGraph of the step (default) or launch eagerly")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="decode",
                     help="decode (default) is the configuration the headline metric is quoted on")
+    ap.add_argument("--detect", action="store_true",
+                    help="switch GPU-side failure detection on (1 s timeout as in the paper): adds "
+                         "the signal kernel after dispatch and the bounded wait before combine")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--calib", action="store_true",
                     help="first launch 5 plain copy kernels of 512 MiB (k_calibration_copy), the "
@@ -179,15 +182,22 @@ def main():
     def combine():
         ctx.combine(y, w, out, T, stream=stream)
 
+    if args.detect:
+        ctx.set_detection(1_000_000_000)
+
     def step():
         layout()
         dispatch()
+        if args.detect:   # the expert stage (here: nothing) announces its outputs
+            ctx.signal_experts_done(stream)
         combine()
 
     layout()
     dispatch()
     if wl.stub != "identity":
         ctx.expert_stub(wl.stub, recv, y, T, recv_scale=recv_scale, stream=stream)
+    elif args.detect:
+        ctx.signal_experts_done(stream)
     combine()
     stream.synchronize()
     graph = None
@@ -217,6 +227,8 @@ def main():
         layout()
         e[1].record(stream)
         dispatch()
+        if args.detect:
+            ctx.signal_experts_done(stream)
         e[2].record(stream)
         combine()
         e[3].record(stream)
@@ -246,7 +258,8 @@ def main():
         "ms_per_step": ms, "us_per_step": ms * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "u8"}[wl.x_dtype], "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.workload], "mode": args.mode, "step": "dispatch_layout + dispatch + combine",
+        "config": {"workload": WORKLOADS[args.workload], "mode": args.mode,
+                   "failure_detection": bool(args.detect), "step": "dispatch_layout + dispatch + combine",
                    "algorithmic_bytes_per_step": nbytes["total"]},
         "frac_of_hbm_peak": nbytes["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "wall_ms_per_step": wall_ms,

@@ -161,6 +161,37 @@ int eep_combine(eep_ctx* ctx, const void* y, const float* topk_w, void* out, int
 int eep_expert_stub(eep_ctx* ctx, int32_t kind, const void* recv_x, const float* recv_scale,
                     const float* expert_scale, void* y, int32_t T, void* stream);
 
+/* ---- GPU-side failure detection (Sec. 3.4; Sec. 4.1 "Failure detection from
+ * the GPU side"; Fig. 7: "timeout -> set e.active = 0 and continue") ----------
+ * One-GPU emulation of the paper's signal counters.  Every eep_dispatch_layout
+ * advances a device-side step epoch.  The expert stage announces "the outputs of
+ * rank r for this step are there" by storing the epoch into rank r's signal word
+ * (release); eep_combine, when detection is on, first waits -- inside a kernel,
+ * for at most the timeout -- until every ACTIVE rank's signal shows the epoch.
+ * A rank that stays silent is dropped by that kernel: its active bit is cleared
+ * in the device table, its failure is recorded, and the pairs routed to it
+ * contribute nothing to this step's outputs (the paper fails such in-flight
+ * requests, Sec. 3.1).  Later steps, replayed graphs included, route around the
+ * rank with no host action; the host finds out with eep_read_failures, then
+ * repairs the placement (eep_plan_repair, eep_update_placement).
+ * Switching detection on or off changes which kernels eep_combine and
+ * eep_expert_stub launch, so choose before capturing a graph. */
+
+/* timeout_ns = 0 switches detection off (the default); at most 2e9 (2 s; the
+ * paper uses 1 s).  Host-side setting, no GPU work. */
+int eep_set_detection(eep_ctx* ctx, int64_t timeout_ns);
+/* Producer side: marks the current step's expert outputs of every active rank as
+ * arrived.  eep_expert_stub does this itself when detection is on; callers that
+ * run their own expert kernels (or alias y = recv_x) queue it after them. */
+int eep_signal_experts_done(eep_ctx* ctx, void* stream);
+/* Test knob: withhold_host[R], non-zero = that rank never signals (a silent
+ * peer).  This is how a failure is injected on one GPU. */
+int eep_debug_withhold_signal(eep_ctx* ctx, const int32_t* withhold_host, void* stream);
+/* Waits for `stream`, copies the failure report to failed_host[R] (1 = dropped
+ * by a kernel since the last call), folds it into the host's copy of the active
+ * mask and clears the report. */
+int eep_read_failures(eep_ctx* ctx, int32_t* failed_host, void* stream);
+
 /* ---- introspection ------------------------------------------------------ */
 
 /* Device addresses of the context's arrays (all int32, stable for the

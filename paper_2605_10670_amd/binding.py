@@ -68,6 +68,10 @@ def load():
         "eep_host_uncovered_experts": [i32, i32, i32, vp, vp],
         "eep_host_tiling": [i32, i32, vp],
         "eep_plan_repair": [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp],
+        "eep_set_detection": [vp, i64],
+        "eep_signal_experts_done": [vp, vp],
+        "eep_debug_withhold_signal": [vp, vp, vp],
+        "eep_read_failures": [vp, vp, vp],
         "eep_graph_begin": [vp, vp],
         "eep_graph_end": [vp, vp, ctypes.POINTER(vp)],
         "eep_graph_launch": [vp, vp],
@@ -240,6 +244,27 @@ class Context:
         _check(load().eep_expert_stub(self._h, kind, _ptr(recv_x), _ptr(recv_scale),
                                       _ptr(expert_scale), _ptr(y), T, _stream(stream)),
                "eep_expert_stub", self._h)
+
+    # -- GPU-side failure detection -------------------------------------------
+    def set_detection(self, timeout_ns):
+        _check(load().eep_set_detection(self._h, int(timeout_ns)), "eep_set_detection", self._h)
+
+    def signal_experts_done(self, stream=None):
+        _check(load().eep_signal_experts_done(self._h, _stream(stream)),
+               "eep_signal_experts_done", self._h)
+
+    def debug_withhold_signal(self, withhold, stream=None):
+        w = np.ascontiguousarray(withhold, np.int32)
+        if w.size != self.R:
+            raise ValueError("withhold must have R entries")
+        _check(load().eep_debug_withhold_signal(self._h, w.ctypes.data, _stream(stream)),
+               "eep_debug_withhold_signal", self._h)
+
+    def read_failures(self, stream=None):
+        out = np.zeros(self.R, np.int32)
+        _check(load().eep_read_failures(self._h, out.ctypes.data, _stream(stream)),
+               "eep_read_failures", self._h)
+        return out
 
     # -- introspection -------------------------------------------------------
     def view_pointers(self):

@@ -116,7 +116,8 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   int64_t total = 0;
   for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) total += round_up(n[i] > 0 ? n[i] : 1);
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
-  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + round_up(1);
+  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 2 * round_up(1) +
+           3 * round_up(c->R);
   e = hipMalloc(&c->slab, (size_t)total * sizeof(int32_t));
   if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
   int32_t* cur = (int32_t*)c->slab;
@@ -128,7 +129,13 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   c->base_tile = cur; cur += round_up(n_tile);
   c->blk_unc = cur;   cur += round_up(c->max_tiles);
   c->blk_msk = cur;   cur += round_up(c->max_tiles);
-  c->tbl_version = cur;
+  c->tbl_version = cur; cur += round_up(1);
+  c->step_epoch = cur;  cur += round_up(1);
+  c->signal = cur;      cur += round_up(c->R);
+  c->withhold = cur;    cur += round_up(c->R);
+  c->report = cur;
+  c->detect_timeout_ticks = 0;
+  c->wall_clock_khz = 0;
 
   // initial state: every rank live, every slot empty, nothing laid out
   c->h_active.assign(c->R, 1);
@@ -222,7 +229,9 @@ int eep_combine(eep_ctx* c, const void* y, const float* topk_w, void* out, int32
   if (T == 0) return EEP_OK;
   if (!y || !topk_w || !out) return EEP_ERR_INVALID_ARG;
   if (!aligned16(y) || !aligned16(out)) return EEP_ERR_ALIGN;
-  hipError_t e = launch_combine(c, y, topk_w, out, T, (hipStream_t)stream);
+  hipError_t e = hipSuccess;
+  if (c->detect_timeout_ticks > 0) e = launch_await(c, T, (hipStream_t)stream);
+  if (e == hipSuccess) e = launch_combine(c, y, topk_w, out, T, (hipStream_t)stream);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
 
@@ -249,7 +258,62 @@ int eep_expert_stub(eep_ctx* c, int32_t kind, const void* recv_x, const float* r
   }
   hipError_t e =
       launch_stub(c, kind, recv_x, recv_scale, expert_scale, y, T, (hipStream_t)stream);
+  if (e == hipSuccess && c->detect_timeout_ticks > 0) e = launch_signal(c, (hipStream_t)stream);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_set_detection(eep_ctx* c, int64_t timeout_ns) {
+  if (!c || timeout_ns < 0 || timeout_ns > 2000000000LL || c->R > 8192)
+    return EEP_ERR_INVALID_ARG;
+  if (timeout_ns == 0) {
+    c->detect_timeout_ticks = 0;
+    return EEP_OK;
+  }
+  if (c->wall_clock_khz == 0) {
+    int khz = 0;
+    hipError_t e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device);
+    if (e != hipSuccess || khz <= 0) return fail_hip(c, e);
+    c->wall_clock_khz = khz;
+  }
+  int64_t ticks = (timeout_ns * c->wall_clock_khz + 999999) / 1000000;
+  c->detect_timeout_ticks = ticks > 0 ? ticks : 1;
+  return EEP_OK;
+}
+
+int eep_signal_experts_done(eep_ctx* c, void* stream) {
+  if (!c) return EEP_ERR_INVALID_ARG;
+  hipError_t e = launch_signal(c, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_debug_withhold_signal(eep_ctx* c, const int32_t* withhold_host, void* stream) {
+  if (!c || !withhold_host) return EEP_ERR_INVALID_ARG;
+  std::vector<int32_t> w(c->R);
+  for (int r = 0; r < c->R; ++r) w[r] = withhold_host[r] != 0;
+  hipError_t e = launch_patch(c->withhold, w.data(), c->R, nullptr, 0, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_read_failures(eep_ctx* c, int32_t* failed_host, void* stream) {
+  if (!c || !failed_host) return EEP_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipStreamSynchronize(st);
+  if (e == hipSuccess)
+    e = hipMemcpy(failed_host, c->report, sizeof(int32_t) * c->R, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail_hip(c, e);
+  bool any = false;
+  for (int r = 0; r < c->R; ++r) {
+    failed_host[r] = failed_host[r] != 0;
+    if (failed_host[r]) {
+      c->h_active[r] = 0;  // the kernel already cleared the device copy
+      any = true;
+    }
+  }
+  if (any) {
+    e = launch_fill(c->report, 0, c->R, st);
+    if (e != hipSuccess) return fail_hip(c, e);
+  }
+  return EEP_OK;
 }
 
 int eep_get_view(eep_ctx* c, eep_view* out) {

@@ -63,6 +63,12 @@ struct eep_ctx {
   int32_t *slot_of, *row_of, *src_of, *count, *offset, *rank_count, *rank_offset, *cnt_src, *status;
   // per-step scratch
   int32_t *cnt_tile, *base_tile, *blk_unc, *blk_msk;
+  // GPU-side failure detection: step counter, per-rank arrival word (holds the
+  // epoch of the last step whose expert outputs arrived), test knob that mutes
+  // a rank, failure report written by the waiting kernel
+  int32_t *step_epoch, *signal, *withhold, *report;
+  int64_t detect_timeout_ticks;  // 0 = detection off
+  int wall_clock_khz;
 
   // host shadows of the tables (coverage is validated without touching the GPU)
   std::vector<int32_t> h_active, h_p2l;
@@ -87,6 +93,9 @@ hipError_t launch_combine(eep_ctx* c, const void* y, const float* w, void* out, 
                           hipStream_t st);
 hipError_t launch_stub(eep_ctx* c, int kind, const void* recv_x, const float* recv_scale,
                        const float* expert_scale, void* y, int T, hipStream_t st);
+// detect.hip
+hipError_t launch_signal(eep_ctx* c, hipStream_t st);
+hipError_t launch_await(eep_ctx* c, int T, hipStream_t st);
 // tables.hip
 hipError_t launch_patch(int32_t* dst, const int32_t* src_host, int n, int32_t* version_dst,
                         int32_t version, hipStream_t st);

@@ -188,7 +188,8 @@ __device__ inline void write_step_tables(const int32_t* s_count, const int32_t* 
                                          int32_t* __restrict__ count, int32_t* __restrict__ offset,
                                          int32_t* __restrict__ rank_count,
                                          int32_t* __restrict__ rank_offset,
-                                         int32_t* __restrict__ status, int R, int S, int P) {
+                                         int32_t* __restrict__ status,
+                                         int32_t* __restrict__ step_epoch, int R, int S, int P) {
   const int tid = threadIdx.x;
   for (int p = tid; p <= P; p += NT) {
     offset[p] = s_offset[p];
@@ -204,6 +205,7 @@ __device__ inline void write_step_tables(const int32_t* s_count, const int32_t* 
     status[1] = dropped_unc;
     status[2] = dropped_msk;
     status[3] = version;
+    *step_epoch = *step_epoch + 1;  // one increment per step, on the device (graph replays too)
   }
 }
 
@@ -225,8 +227,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
     const int32_t* __restrict__ slot_of, int32_t* __restrict__ row_of,
     int32_t* __restrict__ src_of, int32_t* __restrict__ count, int32_t* __restrict__ offset,
     int32_t* __restrict__ rank_count, int32_t* __restrict__ rank_offset,
-    int32_t* __restrict__ cnt_src, int32_t* __restrict__ status, int k_rt, int num_tiles,
-    int tokens_per_rank, int tiles_per_rank, int tile_tokens, int R, int S, int P) {
+    int32_t* __restrict__ cnt_src, int32_t* __restrict__ status,
+    int32_t* __restrict__ step_epoch, int k_rt, int num_tiles, int tokens_per_rank,
+    int tiles_per_rank, int tile_tokens, int R, int S, int P) {
   const int k = KC > 0 ? KC : k_rt;
   extern __shared__ int32_t smem[];
   int32_t* s_count = smem;           // [P]   pairs per slot, all tiles
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
   }
   if (b == 0)
     write_step_tables<kFusedThreads>(s_count, s_offset, s_drop[0], s_drop[1], version, count,
-                                     offset, rank_count, rank_offset, status, R, S, P);
+                                     offset, rank_count, rank_offset, status, step_epoch, R, S, P);
 }
 
 // ---------------------------------------------------------------------------
@@ -318,7 +321,8 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(
     const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
     int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
     int32_t* __restrict__ rank_offset, int32_t* __restrict__ pre_tile,
-    int32_t* __restrict__ status, int num_tiles, int R, int S, int P) {
+    int32_t* __restrict__ status, int32_t* __restrict__ step_epoch, int num_tiles, int R, int S,
+    int P) {
   extern __shared__ int32_t smem[];
   int32_t* s_count = smem;           // [P]
   int32_t* s_offset = s_count + P;   // [P+1]
@@ -353,7 +357,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(
   if (dm) atomicAdd(&s_drop[1], dm);
   block_exclusive_scan<kScanThreads>(s_count, s_offset, s_wave, P);
   write_step_tables<kScanThreads>(s_count, s_offset, s_drop[0], s_drop[1], version, count, offset,
-                                  rank_count, rank_offset, status, R, S, P);
+                                  rank_count, rank_offset, status, step_epoch, R, S, P);
 }
 
 template <int KC>
@@ -395,7 +399,7 @@ __global__ __launch_bounds__(256) void k_empty_step(
     const int32_t* __restrict__ tbl_version, int32_t* __restrict__ count,
     int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
     int32_t* __restrict__ rank_offset, int32_t* __restrict__ cnt_src,
-    int32_t* __restrict__ status, int R, int P) {
+    int32_t* __restrict__ status, int32_t* __restrict__ step_epoch, int R, int P) {
   for (int p = threadIdx.x; p <= P; p += 256) {
     offset[p] = 0;
     if (p < P) count[p] = 0;
@@ -408,6 +412,7 @@ __global__ __launch_bounds__(256) void k_empty_step(
   if (threadIdx.x == 0) {
     status[0] = status[1] = status[2] = 0;
     status[3] = *tbl_version;
+    *step_epoch = *step_epoch + 1;
   }
 }
 
@@ -416,8 +421,8 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
   const bool k8 = c->k == 8;
   if (g.num_tiles == 0) {
     hipLaunchKernelGGL(k_empty_step, dim3(1), dim3(256), 0, st, c->tbl_version, c->count,
-                       c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status, c->R,
-                       c->P);
+                       c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
+                       c->step_epoch, c->R, c->P);
     return hipGetLastError();
   }
   {
@@ -437,14 +442,15 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
     hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kFusedThreads), lds, st, c->cnt_tile,
                        c->blk_unc, c->blk_msk, c->tbl_version, c->slot_of, c->row_of, c->src_of,
                        c->count, c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
-                       c->k, g.num_tiles, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, c->R,
+                       c->step_epoch, c->k, g.num_tiles, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, c->R,
                        c->S, c->P);
     return hipGetLastError();
   }
   size_t lds_scan = sizeof(int32_t) * ((size_t)2 * c->P + 1);
   hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), lds_scan, st, c->cnt_tile, c->blk_unc,
                      c->blk_msk, c->tbl_version, c->count, c->offset, c->rank_count,
-                     c->rank_offset, c->base_tile, c->status, g.num_tiles, c->R, c->S, c->P);
+                     c->rank_offset, c->base_tile, c->status, c->step_epoch, g.num_tiles, c->R, c->S,
+                     c->P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   int total_pairs = T * c->k;
