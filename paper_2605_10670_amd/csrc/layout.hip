@@ -32,7 +32,7 @@
 
 namespace eep {
 
-constexpr int kMapThreads = 512;
+constexpr int kMapThreads = 1024;
 constexpr int kScanThreads = 1024;
 constexpr int kPosThreads = 256;
 
