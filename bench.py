@@ -54,7 +54,7 @@ def time_events(stream, fn, reps):
     return e0.elapsed_time(e1) / reps  # ms
 
 
-def cpu_baseline(wl, bytes_total, budget_s=20.0):
+def cpu_baseline(wl, bytes_total, quant=False, budget_s=20.0):
     """The oracle as it stands (single thread) on the same workload: the same
     three calls as the GPU step (layout, pack, combine); y comes from outside."""
     import oracle
@@ -72,7 +72,12 @@ def cpu_baseline(wl, bytes_total, budget_s=20.0):
         t0 = time.perf_counter()
         lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim,
                                  oracle.SPREAD)
-        recv = oracle.pack(wl.x, lay["row_of"])
+        if quant:
+            q, sc = oracle.quantize_e4m3(wl.x, 128)
+            recv = oracle.pack(q, lay["row_of"])
+            oracle.pack(sc, lay["row_of"])
+        else:
+            recv = oracle.pack(wl.x, lay["row_of"])
         if wl.x_scale is not None:
             oracle.pack(wl.x_scale, lay["row_of"])
         oracle.combine(recv if y is None else y, ydt, wl.topk_w, lay["row_of"])
@@ -92,6 +97,8 @@ WORKLOADS = {
                            "Zipf(1.2)-skewed logits: T=4096, H=7168 bf16, E=256, top-8"),
     "prefill_fp8": ("dsv3-prefill: T=16384, H=7168 fp8 e4m3 + fp32 scale/128 dispatch, bf16 combine, "
                     "E=256, top-8, ranks 7 and 20 failed"),
+    "decode_quant": ("dsv3-decode with quantise-on-dispatch: T=4096, H=7168, bf16 tokens -> fp8 e4m3 "
+                     "+ fp32 scale/128 receive rows (eep_dispatch_quant), bf16 combine, all live"),
     "churn": "qwen3-moe-like: T=2048, H=4096 bf16, E=128, top-8, R=16, 8+1 slots/rank, all live",
 }
 BYTES_OF = {"f32": 4, "bf16": 2, "fp8": 1}
@@ -137,8 +144,11 @@ def main():
     copy_gbs = 2 * a.numel() / (time_events(stream, copy, 10) * 1e-3) / 1e9
     del a, b
 
-    if args.workload == "decode":
+    quant = args.workload == "decode_quant"
+    if args.workload in ("decode", "decode_quant"):
         wl = synth.decode()
+        if quant:   # receive rows are fp8 + scales; the stand-in dequantises them once, untimed
+            wl.x_dtype, wl.stub = "fp8", "dequant"
     elif args.workload == "decode_failed_zipf":
         wl = synth.decode_failed_zipf()
     elif args.workload == "prefill_fp8":
@@ -147,9 +157,13 @@ def main():
         wl = synth.churn_inputs(1)[0]
         wl.stub = "identity"
     T, k, H = wl.T, wl.k, wl.H
-    scale_row = (H // 128) * 4 if wl.x_scale is not None else 0
+    scale_row = (H // 128) * 4 if (wl.x_scale is not None or quant) else 0
     nbytes = algorithmic_bytes(T, k, H, BYTES_OF[wl.x_dtype], BYTES_OF[wl.y_dtype],
                                BYTES_OF[wl.out_dtype], scale_row)
+    if quant:   # the token rows are read as bf16 (2 B) and carry no scales on the way in
+        delta = T * H * (2 - 1) - T * scale_row
+        nbytes["dispatch"] += delta
+        nbytes["total"] += delta
 
     ctx = binding.Context(num_ranks=wl.R, slots_per_rank=wl.S, primary_slots=wl.S_prim,
                           num_logical=wl.E, max_tokens=T, topk=k, hidden=H, x_dtype=wl.x_dtype,
@@ -164,7 +178,7 @@ def main():
     x_scale = dev(wl.x_scale) if wl.x_scale is not None else None
     recv = torch.empty((T * k, H), dtype=tdt[wl.x_dtype], device="cuda")
     recv_scale = (torch.empty((T * k, H // 128), dtype=torch.float32, device="cuda")
-                  if x_scale is not None else None)
+                  if (x_scale is not None or quant) else None)
     # identity expert: y aliases the receive buffer; otherwise the stand-in fills y once, untimed
     y = recv if wl.stub == "identity" else torch.empty((T * k, H), dtype=tdt[wl.y_dtype],
                                                        device="cuda")
@@ -177,7 +191,10 @@ def main():
         ctx.dispatch_layout(idx, T, stream)
 
     def dispatch():
-        ctx.dispatch(x, recv, T, x_scale, recv_scale, stream)
+        if quant:
+            ctx.dispatch_quant(x, recv, recv_scale, T, stream)
+        else:
+            ctx.dispatch(x, recv, T, x_scale, recv_scale, stream)
 
     def combine():
         ctx.combine(y, w, out, T, stream=stream)
@@ -239,7 +256,7 @@ def main():
     if graph is not None:
         graph.destroy()
 
-    kernel_of = {"dispatch": "k_pack", "combine": "k_combine"}
+    kernel_of = {"dispatch": "k_pack_quant" if quant else "k_pack", "combine": "k_combine"}
     kernels = {}
     for stage, kname in kernel_of.items():
         gbs = nbytes[stage] / (stage_ms[stage] * 1e-3) / 1e9
@@ -275,7 +292,7 @@ def main():
         "kernels": kernels,
     }
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(wl, nbytes["total"])
+        result["cpu_baseline"] = cpu_baseline(wl, nbytes["total"], quant)
     ctx.destroy()
     print(json.dumps(result))
 

@@ -143,6 +143,17 @@ int eep_dispatch_layout(eep_ctx* ctx, const int32_t* topk_idx, int32_t T, void* 
 int eep_dispatch(eep_ctx* ctx, const void* x, const float* x_scale, void* recv_x,
                  float* recv_scale, int32_t T, void* stream);
 
+/* Variant of eep_dispatch with the fp8 quantisation fused in (a data-path variant
+ * of the kind Sec. 4.1 leaves to prior work).  The context's x_dtype must be
+ * FP8_E4M3 with scale_group a power-of-two multiple of 16 (16..1024); x_bf16 is
+ * device bf16 [T, H].  Per token and per group of scale_group channels:
+ * scale = max|x| / 448 in fp32 (1 if the group is all zero),
+ * code = e4m3fn(x / scale), round to nearest even, saturating;
+ * recv_x[row, :] gets the codes and recv_scale[row, :] the scales of the token,
+ * for each of its routed rows.  Same call order and errors as eep_dispatch. */
+int eep_dispatch_quant(eep_ctx* ctx, const void* x_bf16, void* recv_x, float* recv_scale,
+                       int32_t T, void* stream);
+
 /* out[t, :] = round( sum over routed j, ascending, of w[t, j] * y[row_of[t, j], :] ),
  * accumulated in fp32 with one fused multiply-add per term, starting from 0
  * (Sec. 4.1: combine reduces the expert outputs).  y: device [T*k, H] y_dtype;

@@ -156,6 +156,23 @@ def e4m3_to_f32(q):
     return out
 
 
+def f32_to_e4m3(x):
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty(x.shape, np.uint8)
+    lib().eeo_f32_to_e4m3_array(ctypes.c_int64(x.size), _p(x), _p(out))
+    return out
+
+
+def quantize_e4m3(x_bf16_bits, group=128):
+    """Quantise-on-dispatch definition: bf16 bits [T,H] -> (codes uint8 [T,H], scale f32 [T,H/group])."""
+    x = np.ascontiguousarray(x_bf16_bits, np.uint16)
+    T, H = x.shape
+    q = np.empty((T, H), np.uint8)
+    scale = np.empty((T, H // group), np.float32)
+    lib().eeo_quantize_e4m3(T, H, group, _p(x), _p(q), _p(scale))
+    return q, scale
+
+
 def step_layout(topk_idx, p2l, active, E, R, S, S_prim, policy):
     """O1-O5 in one call -> dict with slot_of, counters and every layout array."""
     off, lst = tables(p2l, E, S, S_prim)

@@ -74,6 +74,51 @@ float eeo_e4m3_to_f32(uint8_t q) {
   return (float)(sign ? -v : v);
 }
 
+/* binary32 -> e4m3fn code: nearest representable value, ties to the even code,
+ * magnitudes of 448 and above saturate to 448 (0x7e); NaN -> 0x7f.
+ * Written from the format's definition: find the binade with frexp, count
+ * eighths of the binade (or 2^-9 steps below 2^-6), round with nearbyint. */
+uint8_t eeo_f32_to_e4m3(float f) {
+  uint8_t sign = signbit(f) ? 0x80 : 0x00;
+  if (isnan(f)) return sign | 0x7f;
+  double mag = fabs((double)f);
+  if (mag >= 448.0) return sign | 0x7e;
+  if (mag < ldexp(1.0, -6)) {
+    int n = (int)nearbyint(mag * 512.0); /* steps of 2^-9; 8 steps = 2^-6, code 0x08 */
+    return sign | (uint8_t)n;
+  }
+  int ex;
+  (void)frexp(mag, &ex); /* mag = m * 2^ex, m in [0.5, 1) */
+  int E = ex - 1;        /* mag = (1 + frac) * 2^E */
+  int n = (int)nearbyint((mag / ldexp(1.0, E) - 1.0) * 8.0);
+  if (n == 8) { n = 0; E += 1; }
+  int code = ((E + 7) << 3) | n;
+  if (code > 0x7e) code = 0x7e;
+  return sign | (uint8_t)code;
+}
+
+/* Quantise-on-dispatch variant: per token and per `group` channels,
+ * scale = max|x| / 448 in binary32 (1 if all zero), code = e4m3(x / scale) with
+ * the division in binary32.  x: bf16 [T,H] -> q: codes [T,H], scale [T,H/group]. */
+void eeo_quantize_e4m3(int T, int H, int group, const uint16_t* x, uint8_t* q, float* scale) {
+  int G = H / group;
+  for (int t = 0; t < T; ++t)
+    for (int g = 0; g < G; ++g) {
+      float amax = 0.0f;
+      for (int c = 0; c < group; ++c) {
+        float v = fabsf(eeo_bf16_to_f32(x[(int64_t)t * H + g * group + c]));
+        if (v > amax) amax = v;
+      }
+      float sc = amax / 448.0f;
+      if (sc == 0.0f) sc = 1.0f;
+      scale[(int64_t)t * G + g] = sc;
+      for (int c = 0; c < group; ++c) {
+        int64_t i = (int64_t)t * H + g * group + c;
+        q[i] = eeo_f32_to_e4m3(eeo_bf16_to_f32(x[i]) / sc);
+      }
+    }
+}
+
 /* ---------- O1: expert-location metadata ------------------------------------
  * p2l[P]: logical expert of each physical slot p = r*S + s (-1 = empty).
  * Output: for each logical expert e the list of its replicas in canonical
@@ -282,6 +327,9 @@ void eeo_bf16_to_f32_array(int64_t n, const uint16_t* in, float* out) {
 }
 void eeo_f32_to_bf16_array(int64_t n, const float* in, uint16_t* out) {
   for (int64_t i = 0; i < n; ++i) out[i] = eeo_f32_to_bf16(in[i]);
+}
+void eeo_f32_to_e4m3_array(int64_t n, const float* in, uint8_t* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = eeo_f32_to_e4m3(in[i]);
 }
 void eeo_e4m3_to_f32_array(int64_t n, const uint8_t* in, float* out) {
   for (int64_t i = 0; i < n; ++i) out[i] = eeo_e4m3_to_f32(in[i]);

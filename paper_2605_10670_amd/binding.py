@@ -58,6 +58,7 @@ def load():
         "eep_update_placement": [vp, vp, vp],
         "eep_dispatch_layout": [vp, vp, i32, vp],
         "eep_dispatch": [vp, vp, vp, vp, vp, i32, vp],
+        "eep_dispatch_quant": [vp, vp, vp, vp, i32, vp],
         "eep_combine": [vp, vp, vp, vp, i32, vp],
         "eep_expert_stub": [vp, i32, vp, vp, vp, vp, i32, vp],
         "eep_get_view": [vp, ctypes.POINTER(_View)],
@@ -234,6 +235,10 @@ class Context:
     def dispatch(self, x, recv_x, T, x_scale=None, recv_scale=None, stream=None):
         _check(load().eep_dispatch(self._h, _ptr(x), _ptr(x_scale), _ptr(recv_x),
                                    _ptr(recv_scale), T, _stream(stream)), "eep_dispatch", self._h)
+
+    def dispatch_quant(self, x_bf16, recv_x, recv_scale, T, stream=None):
+        _check(load().eep_dispatch_quant(self._h, _ptr(x_bf16), _ptr(recv_x), _ptr(recv_scale), T,
+                                         _stream(stream)), "eep_dispatch_quant", self._h)
 
     def combine(self, y, topk_w, out, T, stream=None):
         _check(load().eep_combine(self._h, _ptr(y), _ptr(topk_w), _ptr(out), T, _stream(stream)),

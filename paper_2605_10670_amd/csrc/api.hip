@@ -222,6 +222,23 @@ int eep_dispatch(eep_ctx* c, const void* x, const float* x_scale, void* recv_x, 
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
 
+int eep_dispatch_quant(eep_ctx* c, const void* x_bf16, void* recv_x, float* recv_scale, int32_t T,
+                       void* stream) {
+  if (!c || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;
+  if (c->cfg.x_dtype != EEP_FP8_E4M3) return EEP_ERR_INVALID_ARG;
+  const int lanes_per_group = c->cfg.scale_group / 16;
+  if (lanes_per_group > 64 || (lanes_per_group & (lanes_per_group - 1)) != 0 ||
+      c->H / c->cfg.scale_group > 8192)
+    return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T) return EEP_ERR_STATE;
+  if (T == 0) return EEP_OK;
+  if (!x_bf16 || !recv_x || !recv_scale) return EEP_ERR_INVALID_ARG;
+  if (!aligned16(x_bf16) || !aligned16(recv_x) || ((uintptr_t)recv_scale & 3u))
+    return EEP_ERR_ALIGN;
+  hipError_t e = launch_pack_quant(c, x_bf16, recv_x, recv_scale, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
 int eep_combine(eep_ctx* c, const void* y, const float* topk_w, void* out, int32_t T,
                 void* stream) {
   if (!c || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;

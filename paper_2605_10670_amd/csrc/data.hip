@@ -108,6 +108,118 @@ __device__ inline float e4m3_to_f32(uint32_t q) {
   return __uint_as_float(bits | sign);
 }
 
+// binary32 -> OCP e4m3fn byte, round to nearest even, saturating at +-448
+// (NaN -> 0x7f).  Normal results round the 23-bit significand to 3 bits with an
+// integer add so that a carry moves into the exponent; results below 2^-6 are
+// multiples of 2^-9.
+__device__ inline uint32_t f32_to_e4m3(float f) {
+  uint32_t u = __float_as_uint(f);
+  uint32_t sign = (u >> 24) & 0x80u;
+  uint32_t a = u & 0x7fffffffu;
+  if (a > 0x7f800000u) return sign | 0x7fu;      // NaN
+  if (a >= 0x43e00000u) return sign | 0x7eu;     // |f| >= 448: saturate
+  uint32_t code;
+  if (a < 0x3c800000u) {                         // |f| < 2^-6: subnormal range
+    float scaled = __uint_as_float(a) * 512.0f;  // exact; in [0, 8)
+    code = (uint32_t)__float2int_rn(scaled);     // ties to even; 8 is the smallest normal
+  } else {
+    uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);
+    code = (r >> 20) - ((127u - 7u) << 3);
+    if (code > 0x7eu) code = 0x7eu;              // 448 < |f| rounded past the top
+  }
+  return sign | code;
+}
+
+// ---------------------------------------------------------------------------
+// pack with quantisation fused in (a data-path variant the paper's Sec. 4.1
+// leaves to prior work): x is bf16, the receive rows are e4m3 codes plus one
+// fp32 scale per `group` channels.  Per token and group: scale = max|x| / 448
+// (1 if the group is all zero), code = e4m3(x / scale).  One wavefront per
+// token; a lane owns 16 consecutive channels (32 bytes in, 16 bytes out), so
+// the lanes of a group are neighbours and the group maximum is a few
+// xor-shuffles.  The token is quantised once and stored to its k rows.
+// ---------------------------------------------------------------------------
+constexpr int kQuantVecs = 7;  // 16-channel vectors per lane per pass (7 * 64 * 16 = 7168)
+
+__global__ __launch_bounds__(64) void k_pack_quant(const u32x4* __restrict__ x,
+                                                   u32x4* __restrict__ recv_q,
+                                                   float* __restrict__ recv_scale,
+                                                   const int32_t* __restrict__ row_of, int k,
+                                                   int out_vecs, int lanes_per_group,
+                                                   int groups) {
+  extern __shared__ float s_scale[];  // [groups] scales of this token
+  const int t = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int32_t* rows = row_of + (int64_t)t * k;
+  const u32x4* src = x + (int64_t)t * out_vecs * 2;
+  for (int w0 = 0; w0 < out_vecs; w0 += 64 * kQuantVecs) {
+    u32x4 in[kQuantVecs][2];
+#pragma unroll
+    for (int u = 0; u < kQuantVecs; ++u) {
+      int w = w0 + u * 64 + lane;
+      if (w < out_vecs) {
+        in[u][0] = __builtin_nontemporal_load(&src[2 * w]);
+        in[u][1] = __builtin_nontemporal_load(&src[2 * w + 1]);
+      } else {
+        in[u][0] = in[u][1] = u32x4{0, 0, 0, 0};
+      }
+    }
+    u32x4 q[kQuantVecs];
+#pragma unroll
+    for (int u = 0; u < kQuantVecs; ++u) {
+      int w = w0 + u * 64 + lane;
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint32_t d = in[u][i >> 2][i & 3];
+        v[2 * i] = bf16_lo(d);
+        v[2 * i + 1] = bf16_hi(d);
+      }
+      float amax = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[i]));
+      for (int m = 1; m < lanes_per_group; m <<= 1) amax = fmaxf(amax, __shfl_xor(amax, m, 64));
+      float scale = amax / 448.0f;
+      if (scale == 0.0f) scale = 1.0f;
+      if (w < out_vecs && (lane & (lanes_per_group - 1)) == 0) s_scale[w / lanes_per_group] = scale;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        q[u][i] = f32_to_e4m3(v[4 * i] / scale) | (f32_to_e4m3(v[4 * i + 1] / scale) << 8) |
+                  (f32_to_e4m3(v[4 * i + 2] / scale) << 16) |
+                  (f32_to_e4m3(v[4 * i + 3] / scale) << 24);
+    }
+    for (int j = 0; j < k; ++j) {
+      int row = rows[j];
+      if (row < 0) continue;
+      u32x4* dst = recv_q + (int64_t)row * out_vecs;
+#pragma unroll
+      for (int u = 0; u < kQuantVecs; ++u) {
+        int w = w0 + u * 64 + lane;
+        if (w < out_vecs) store_through(&dst[w], q[u]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int g = lane; g < groups; g += 64) {
+    float sc = s_scale[g];
+    for (int j = 0; j < k; ++j) {
+      int row = rows[j];
+      if (row >= 0) recv_scale[(int64_t)row * groups + g] = sc;
+    }
+  }
+}
+
+hipError_t launch_pack_quant(eep_ctx* c, const void* x_bf16, void* recv_q, float* recv_scale, int T,
+                             hipStream_t st) {
+  if (T == 0) return hipSuccess;
+  int out_vecs = c->H / 16;
+  int groups = c->H / c->cfg.scale_group;
+  hipLaunchKernelGGL(k_pack_quant, dim3(T), dim3(64), sizeof(float) * groups, st,
+                     (const u32x4*)x_bf16, (u32x4*)recv_q, recv_scale, c->row_of, c->k, out_vecs,
+                     c->cfg.scale_group / 16, groups);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // combine: out[t] = sum_j w[t,j] * y[row_of[t,j]], fp32 fused multiply-add chain
 // in ascending j.  A lane owns 16-byte columns of the row and issues the k row

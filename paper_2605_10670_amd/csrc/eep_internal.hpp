@@ -89,6 +89,8 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
 // data.hip
 hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
                        float* recv_scale, int T, hipStream_t st);
+hipError_t launch_pack_quant(eep_ctx* c, const void* x_bf16, void* recv_q, float* recv_scale, int T,
+                             hipStream_t st);
 hipError_t launch_combine(eep_ctx* c, const void* y, const float* w, void* out, int T,
                           hipStream_t st);
 hipError_t launch_stub(eep_ctx* c, int kind, const void* recv_x, const float* recv_scale,

@@ -231,6 +231,64 @@ def test_prefill_fp8_full_size_sampled(oracle):
         ctx.destroy()
 
 
+@pytest.mark.parametrize("T,H,group", [(256, 1024, 128), (4096, 7168, 128), (64, 1024, 64),
+                                       (96, 256, 16)])
+def test_dispatch_with_fused_quantisation(oracle, T, H, group):
+    """bf16 tokens in, e4m3 codes + fp32 scales out (quantise-on-dispatch
+    variant): codes and scales of every routed row bit-equal to the oracle's
+    quantiser followed by its pack; then dequantising stand-in and combine."""
+    wl = synth.decode(T=T, H=H)
+    rng = np.random.default_rng(T)
+    xf = synth.bf16_bits_to_f32(wl.x) * np.exp(rng.standard_normal((T, 1))).astype(np.float32)
+    xf[3, :group] = 0.0                                  # an all-zero group
+    xf[5, 7] = 3.0e4                                     # an outlier that sets its group's scale
+    xb = synth.f32_to_bf16_bits(xf)
+    failed = (9,)
+    p2l = synth.repaired_placement(wl.p2l, failed, wl.R, wl.S_prim, wl.S_red)
+    active = synth.active_mask(wl.R, failed)
+    ctx = binding.Context(num_ranks=wl.R, slots_per_rank=wl.S, primary_slots=wl.S_prim,
+                          num_logical=wl.E, max_tokens=T, topk=wl.k, hidden=H, x_dtype="fp8",
+                          y_dtype="bf16", out_dtype="bf16", scale_group=group)
+    try:
+        gu.apply_tables(ctx, p2l, active)
+        idx, w, x = gu.to_dev(wl.topk_idx), gu.to_dev(wl.topk_w), gu.to_dev(xb)
+        recv = torch.zeros((T * wl.k, H), dtype=torch.uint8, device="cuda")
+        recv_scale = torch.zeros((T * wl.k, H // group), dtype=torch.float32, device="cuda")
+        y = torch.zeros((T * wl.k, H), dtype=torch.int16, device="cuda")
+        out = torch.zeros((T, H), dtype=torch.int16, device="cuda")
+        ctx.dispatch_layout(idx, T)
+        ctx.dispatch_quant(x, recv, recv_scale, T)
+        ctx.expert_stub("dequant", recv, y, T, recv_scale=recv_scale)
+        ctx.combine(y, w, out, T)
+        torch.cuda.synchronize()
+        lay = oracle.step_layout(wl.topk_idx, p2l, active, wl.E, wl.R, wl.S, wl.S_prim, 0)
+        got = ctx.read_layout(T)
+        gu.assert_layout_equal(got, lay, T, wl.k)
+        N = lay["N"]
+        q, sc = oracle.quantize_e4m3(xb, group)
+        want_q, want_sc = oracle.pack(q, lay["row_of"]), oracle.pack(sc, lay["row_of"])
+        assert np.array_equal(recv.cpu().numpy()[:N], want_q[:N]), "fp8 codes"
+        assert np.array_equal(recv_scale.cpu().numpy()[:N].view(np.uint32),
+                              want_sc[:N].view(np.uint32)), "scales"
+        want_y = oracle.stub_dequant(want_q, want_sc, N, group)
+        assert np.array_equal(gu.to_host(y, np.uint16)[:N], want_y[:N])
+        chain = oracle.f32_to_bf16(oracle.combine_chain32(want_y, oracle.BF16, wl.topk_w,
+                                                          lay["row_of"]))
+        out_h = gu.to_host(out, np.uint16)
+        assert np.array_equal(out_h, chain)
+        gu.check_combine(out_h, "bf16", oracle.combine(want_y, oracle.BF16, wl.topk_w,
+                                                       lay["row_of"]))
+        # end to end the quantisation error stays at the fp8 level: out ~= x
+        ref = synth.bf16_bits_to_f32(xb).astype(np.float64)
+        err = np.abs(gu.bf16_to_f64(out_h) - ref)
+        amax = np.abs(ref.reshape(T, H // group, group)).max(2, keepdims=True)
+        # half an e4m3 step at the top binade (16/448 of the group maximum) plus two bf16 roundings
+        ok = err.reshape(T, H // group, group) <= amax / 448 * 20 + 1e-30
+        assert ok.all(), f"{(~ok).sum()} elements off by more than the fp8 step"
+    finally:
+        ctx.destroy()
+
+
 def test_decode_full_size(oracle):
     """DeepSeek-V3 decode shape at full size, every output compared."""
     wl = synth.decode()

@@ -226,3 +226,41 @@ def test_stub_scale_bf16_and_dequant_match_torch(oracle):
     assert np.array_equal(yd[:5], want_d[:5]) and (yd[5:] == 0).all()
     # and the quantiser is sane: dequantised values are close to the originals
     assert np.abs(deq.numpy() - big).max() <= np.abs(big).max() / 448 * 16 + 1e-6
+
+
+def test_e4m3_encoder_matches_torch_and_the_format(oracle):
+    """Pins for the quantise-on-dispatch definition: torch's float8_e4m3fn cast
+    (round to nearest even) on every in-range value class, exact ties, the
+    saturation rule, and the independent searchsorted quantiser of synth."""
+    rng = np.random.default_rng(13)
+    codes = np.arange(256, dtype=np.uint8)
+    vals = oracle.e4m3_to_f32(codes)
+    finite = ~np.isnan(vals)
+    assert np.array_equal(oracle.f32_to_e4m3(vals[finite]), codes[finite])   # round trip
+    pos = np.sort(vals[finite & (codes < 0x80)])
+    mids = ((pos[:-1].astype(np.float64) + pos[1:]) / 2).astype(np.float32)  # exact in binary32
+    x = np.concatenate([rng.standard_normal(100000).astype(np.float32) * 100,
+                        rng.standard_normal(100000).astype(np.float32) * 0.01,
+                        mids, -mids, np.nextafter(mids, np.float32(0)),
+                        np.nextafter(mids, np.float32(1000)),
+                        np.array([0.0, -0.0, 447.9, 448.0, -448.0, 2.0 ** -9, 2.0 ** -10,
+                                  1.5 * 2.0 ** -10, 2.5 * 2.0 ** -9], np.float32)])
+    x = x[np.abs(x) <= 448]
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = oracle.f32_to_e4m3(x)
+    assert np.array_equal(got, want)
+    # ties go to the even code
+    tie_codes = oracle.f32_to_e4m3(mids)
+    assert (tie_codes % 2 == 0).all()
+    # saturation and NaN
+    big = np.array([449.0, 463.9, 464.0, 1e6, np.inf, -500.0, np.nan], np.float32)
+    assert oracle.f32_to_e4m3(big).tolist()[:6] == [0x7E, 0x7E, 0x7E, 0x7E, 0x7E, 0xFE]
+    assert oracle.f32_to_e4m3(big)[6] & 0x7F == 0x7F
+    # whole-tensor definition against the generator's quantiser (a third method)
+    xb = synth.f32_to_bf16_bits(rng.standard_normal((64, 512), dtype=np.float32) * 3)
+    xb[5, 128:256] = 0                                          # an all-zero group
+    q, sc = oracle.quantize_e4m3(xb, 128)
+    q2, sc2 = synth.quantize_e4m3(synth.bf16_bits_to_f32(xb), 128)
+    assert np.array_equal(sc, sc2) and np.array_equal(q, q2)
+    assert sc[5, 1] == 1.0 and (q[5, 128:256] == 0).all()
+    assert np.abs(oracle.e4m3_to_f32(q)).max() == 448.0
