@@ -252,6 +252,8 @@ def main():
     stream.synchronize()
     stage_ms = {name: sum(e[i].elapsed_time(e[i + 1]) for e in ev) / len(ev)
                 for i, name in enumerate(("layout", "dispatch", "combine"))}
+    per_step = sorted(e[0].elapsed_time(e[3]) * 1e3 for e in ev)
+    pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     other_ms = time_events(stream, step, args.steps)   # eager steps, no inner events
     if graph is not None:
         graph.destroy()
@@ -284,6 +286,7 @@ def main():
         "frac_of_copy_ceiling": nbytes["total"] / (ms * 1e-3) / 1e9 / copy_gbs,
         "stages_us": {n: v * 1e3 for n, v in stage_ms.items()},
         "eager_us_per_step": other_ms * 1e3,
+        "eager_step_with_events_us": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["frac"],
                      "traffic": kernels[dom]["traffic"],

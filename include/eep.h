@@ -19,7 +19,8 @@
  *     until the work queued on the stream has finished.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All work is queued on it and no entry point synchronises, except where
- *     stated (eep_create, eep_destroy, eep_read_view, eep_graph_*).
+ *     stated (eep_create, eep_destroy, eep_read_view, eep_read_failures,
+ *     eep_graph_end).
  *   - The context owns the membership/placement tables and the layout arrays.
  *     Their device addresses never change during the context's lifetime:
  *     table updates rewrite contents only (Fig. 4, Fig. 8), which is what lets

@@ -181,6 +181,39 @@ def test_wide_and_odd_shapes(oracle, shape):
     assert got["N"] == T * k
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configurations(oracle, seed):
+    """Seeded random instances: rank/slot/expert counts, top-k, token counts that
+    leave ragged tiles, dtypes, replica policies, random placements with empty
+    slots and multi-replica experts, random masks (coverage not guaranteed, so
+    strict checking is off and uncovered pairs are counted), stray indices."""
+    rng = np.random.default_rng(1000 + seed)
+    R = int(rng.choice([1, 2, 3, 4, 6, 8, 16, 32]))
+    S = int(rng.integers(1, 7))
+    S_prim = int(rng.integers(0, S + 1))
+    E = int(rng.integers(1, R * S + 4))
+    k = int(rng.integers(1, min(E, 12) + 1))
+    T = R * int(rng.choice([1, 2, 5, 31, 64, 100, 129, 200]))
+    xd, yd, od, stub = [("f32", "f32", "f32", "scale"), ("bf16", "bf16", "bf16", "scale"),
+                        ("bf16", "bf16", "f32", "identity"), ("f32", "f32", "bf16", "identity")][seed % 4]
+    H = int(rng.choice([8, 40, 256, 520])) * (1 if xd == "f32" else 2)
+    x32 = rng.standard_normal((T, H), dtype=np.float32)
+    x = x32 if xd == "f32" else synth.f32_to_bf16_bits(x32)
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    idx = idx.copy()
+    idx[rng.random(idx.shape) < 0.03] = -1
+    idx[rng.random(idx.shape) < 0.03] = E + 1
+    p2l = rng.integers(-1, E, size=R * S).astype(np.int32)
+    active = (rng.random(R) < 0.75).astype(np.int32)
+    wl = synth.Workload(f"random-{seed}", T, H, E, k, R, S_prim, S - S_prim, xd, yd, od, stub, (),
+                        idx, w, x, p2l, active,
+                        expert_scale=(0.5 + rng.random(E)).astype(np.float32))
+    got, ref = run_and_compare(oracle, wl, policy=seed % 2, strict=False)
+    assert got["N"] + got["n_uncovered"] + got["n_masked"] == T * k
+    dead = np.nonzero(active == 0)[0]
+    assert got["rank_count"][dead].sum() == 0
+
+
 def test_prefill_fp8_reduced(oracle):
     wl = synth.prefill_fp8(T=1024, H=1024)
     got, _ = run_and_compare(oracle, wl)
