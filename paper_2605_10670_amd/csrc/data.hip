@@ -31,6 +31,11 @@ __device__ inline void store_through(u32x4* p, u32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
 }
 
+// U = 16-byte vectors per lane per pass.  EXACT: the row is a whole number of
+// passes (row_vecs % (64 * U) == 0), so no load or store needs a bounds guard
+// and the compiler keeps all U loads of a pass in flight; otherwise every
+// access is guarded (any row size).
+template <int U, bool EXACT>
 __global__ __launch_bounds__(64) void k_pack(const u32x4* __restrict__ x,
                                              u32x4* __restrict__ recv,
                                              const u32x4* __restrict__ x_scale,
@@ -41,21 +46,28 @@ __global__ __launch_bounds__(64) void k_pack(const u32x4* __restrict__ x,
   const int lane = threadIdx.x;
   const int32_t* rows = row_of + (int64_t)t * k;
   const u32x4* src = x + (int64_t)t * row_vecs;
-  for (int v0 = 0; v0 < row_vecs; v0 += 64 * kPackVecs) {
-    u32x4 buf[kPackVecs];
+  for (int v0 = 0; v0 < row_vecs; v0 += 64 * U) {
+    u32x4 buf[U];
 #pragma unroll
-    for (int u = 0; u < kPackVecs; ++u) {
+    for (int u = 0; u < U; ++u) {
       int v = v0 + u * 64 + lane;
-      if (v < row_vecs) buf[u] = __builtin_nontemporal_load(&src[v]);
+      if (EXACT || v < row_vecs) buf[u] = __builtin_nontemporal_load(&src[v]);
+    }
+    // Touch every loaded register here, so that the waits for the loads sit in
+    // front of the row loop and the stores of consecutive rows stream out
+    // without a wait between them.
+    if (EXACT) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) asm volatile("" ::"v"(buf[u]));
     }
     for (int j = 0; j < k; ++j) {
       int row = rows[j];
       if (row < 0) continue;
       u32x4* dst = recv + (int64_t)row * row_vecs;
 #pragma unroll
-      for (int u = 0; u < kPackVecs; ++u) {
+      for (int u = 0; u < U; ++u) {
         int v = v0 + u * 64 + lane;
-        if (v < row_vecs) store_through(&dst[v], buf[u]);
+        if (EXACT || v < row_vecs) store_through(&dst[v], buf[u]);
       }
     }
   }
@@ -70,15 +82,30 @@ __global__ __launch_bounds__(64) void k_pack(const u32x4* __restrict__ x,
   }
 }
 
+template <int U, bool EXACT>
+static hipError_t launch_pack_t(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
+                                float* recv_scale, int T, hipStream_t st) {
+  hipLaunchKernelGGL((k_pack<U, EXACT>), dim3(T), dim3(64), 0, st, (const u32x4*)x,
+                     (u32x4*)recv_x, (const u32x4*)x_scale, (u32x4*)recv_scale, c->row_of, c->k,
+                     (int)(c->x_row_bytes / 16), (int)(c->scale_row_bytes / 16));
+  return hipGetLastError();
+}
+
 hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
                        float* recv_scale, int T, hipStream_t st) {
   if (T == 0) return hipSuccess;
-  int row_vecs = (int)(c->x_row_bytes / 16);
-  int scale_vecs = (int)(c->scale_row_bytes / 16);
-  hipLaunchKernelGGL(k_pack, dim3(T), dim3(64), 0, st, (const u32x4*)x, (u32x4*)recv_x,
-                     (const u32x4*)x_scale, (u32x4*)recv_scale, c->row_of, c->k, row_vecs,
-                     scale_vecs);
-  return hipGetLastError();
+  const int row_vecs = (int)(c->x_row_bytes / 16);
+  if (row_vecs % 64 == 0) {
+    // the largest pass width <= kPackVecs that divides the row
+    const int per_lane = row_vecs / 64;
+    if (per_lane % 14 == 0) return launch_pack_t<14, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+    if (per_lane % 8 == 0) return launch_pack_t<8, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+    if (per_lane % 7 == 0) return launch_pack_t<7, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+    if (per_lane % 4 == 0) return launch_pack_t<4, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+    if (per_lane % 2 == 0) return launch_pack_t<2, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+    return launch_pack_t<1, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+  }
+  return launch_pack_t<kPackVecs, false>(c, x, x_scale, recv_x, recv_scale, T, st);
 }
 
 // ---------------------------------------------------------------------------
