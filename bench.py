@@ -111,6 +111,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph",
                     help="replay a captured hipGraph of the step (default) or launch eagerly")
+    ap.add_argument("--steps-per-graph", type=int, default=8,
+                    help="steps captured into one hipGraph (a decode forward pass holds one such "
+                         "step per MoE layer in a single graph); reduced to a divisor of --steps")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="decode",
                     help="decode (default) is the configuration the headline metric is quoted on")
     ap.add_argument("--detect", action="store_true",
@@ -218,20 +221,24 @@ def main():
     combine()
     stream.synchronize()
     graph = None
+    spg = 1
     if args.mode == "graph":
+        import math
+        spg = math.gcd(max(1, args.steps_per_graph), args.steps) if args.steps > 0 else 1
         ctx.graph_begin(stream)
-        step()
+        for _ in range(spg):
+            step()
         graph = ctx.graph_end(stream)
         run = lambda: graph.launch(stream)
     else:
         run = step
 
-    for _ in range(args.warmup):
+    for _ in range(-(-args.warmup // spg)):
         run()
     stream.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    ms = time_events(stream, run, args.steps)
+    ms = time_events(stream, run, args.steps // spg) / spg     # exactly args.steps steps
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -278,6 +285,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "u8"}[wl.x_dtype], "data": "synthetic",
         "config": {"workload": WORKLOADS[args.workload], "mode": args.mode,
+                   "steps_per_graph": spg if args.mode == "graph" else None,
                    "failure_detection": bool(args.detect), "step": "dispatch_layout + dispatch + combine",
                    "algorithmic_bytes_per_step": nbytes["total"]},
         "frac_of_hbm_peak": nbytes["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -36,6 +36,24 @@ constexpr int kMapThreads = 1024;
 constexpr int kScanThreads = 1024;
 constexpr int kPosThreads = 256;
 
+// Tile b covers tokens [t0, t0 + ntok) of source rank b / tiles_per_rank; the
+// last tile of a rank may be shorter, and no tile crosses into the next rank.
+struct TileRange {
+  int src_rank, sub_tile, t0, ntok;
+};
+__device__ inline TileRange tile_range(int b, int tokens_per_rank, int tiles_per_rank,
+                                       int tile_tokens) {
+  TileRange r;
+  r.src_rank = b / tiles_per_rank;
+  r.sub_tile = b - r.src_rank * tiles_per_rank;
+  r.t0 = r.src_rank * tokens_per_rank + r.sub_tile * tile_tokens;
+  int t1 = r.t0 + tile_tokens;
+  const int rank_end = (r.src_rank + 1) * tokens_per_rank;
+  if (t1 > rank_end) t1 = rank_end;
+  r.ntok = t1 > r.t0 ? t1 - r.t0 : 0;
+  return r;
+}
+
 // A token can hit a slot at most once: its k logical experts are distinct
 // (repeats are masked) and a slot holds one logical expert.  So one bit per
 // (slot, token of the tile) is enough.
@@ -61,14 +79,9 @@ __global__ __launch_bounds__(kMapThreads) void k_map_count(
 
   const int tid = threadIdx.x;
   const int b = blockIdx.x;
-  const int src_rank = b / tiles_per_rank;
-  const int sub = b - src_rank * tiles_per_rank;
-  const int t0 = src_rank * tokens_per_rank + sub * tile_tokens;
-  int t1 = t0 + tile_tokens;
-  const int rank_end = (src_rank + 1) * tokens_per_rank;
-  if (t1 > rank_end) t1 = rank_end;
-  const int ntok = t1 > t0 ? t1 - t0 : 0;
-  const int npairs = ntok * k;
+  const TileRange tr = tile_range(b, tokens_per_rank, tiles_per_rank, tile_tokens);
+  const int t0 = tr.t0;
+  const int npairs = tr.ntok * k;
   const int64_t g0 = (int64_t)t0 * k;
 
   // every global read of this kernel is issued here, none depends on another
@@ -239,14 +252,10 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
   __shared__ int32_t s_drop[2];
   const int tid = threadIdx.x;
   const int b = blockIdx.x;
-  const int src_rank = b / tiles_per_rank;
-  const int sub_tile = b - src_rank * tiles_per_rank;
-  const int t0 = src_rank * tokens_per_rank + sub_tile * tile_tokens;
-  int t1 = t0 + tile_tokens;
-  const int rank_end = (src_rank + 1) * tokens_per_rank;
-  if (t1 > rank_end) t1 = rank_end;
-  const int npairs = (t1 > t0 ? t1 - t0 : 0) * k;
-  const int g0 = t0 * k;
+  const TileRange tr = tile_range(b, tokens_per_rank, tiles_per_rank, tile_tokens);
+  const int src_rank = tr.src_rank, sub_tile = tr.sub_tile;
+  const int npairs = tr.ntok * k;
+  const int g0 = tr.t0 * k;
   const int first = src_rank * tiles_per_rank;  // tiles [first, first + tiles_per_rank) share
                                                 // this tile's source rank
 
