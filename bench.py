@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by the same counter's reading for the 512 MiB k_calibration_copy
 # (profiles/dsv3_decode_hbm_traffic.md).
-HBM_TRAFFIC_BYTES = {"k_pack": 59290792 + 469762048, "k_combine": 474030206 + 58720256}
+HBM_TRAFFIC_BYTES = {"k_pack": 59276377 + 469762048, "k_combine": 474017735 + 58720256}
 
 
 def algorithmic_bytes(T, k, H, x_bytes, y_bytes, out_bytes, scale_row_bytes=0):
