@@ -42,13 +42,19 @@ _lib = None
 
 
 def load():
-    """Load libeep.so; raises if it has not been built (there is no fallback)."""
+    """Load libeep.so, building it first if it does not exist; raises if that fails
+    (there is no fallback path)."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; "
-                           "g.build()'` (hipcc, gfx950) first")
+        # nothing built yet: compile the HIP sources once (hipcc cross-compiles without a GPU)
+        try:
+            from . import build as _build
+            _build.build()
+        except Exception as exc:
+            raise RuntimeError(f"{LIB_PATH} is missing and could not be built with hipcc ({exc}); "
+                               "there is no fallback path") from exc
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     sig = {

@@ -380,6 +380,53 @@ def test_failure_then_planned_repair_then_rejoin(oracle):
         ctx.destroy()
 
 
+@pytest.mark.parametrize("dtypes", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32")])
+def test_special_values_follow_ieee(oracle, dtypes):
+    """Denormals, infinities, signed zeros and huge values in rows and weights:
+    the fp32 chain must keep denormals (no flush) and round like the oracle, so
+    outputs stay bit-equal; NaNs must appear in exactly the same places."""
+    yd, od = dtypes
+    rng = np.random.default_rng(3)
+    wl = synth.decode(T=64, H=256)
+    specials = np.array([0.0, -0.0, 1e-40, -1e-40, 1.2e-38, 3e38, -3e38, np.inf, -np.inf, 1.0,
+                         2.0 ** -126, 2.0 ** -133, 65504.0, -1.5], np.float32)
+    x32 = rng.choice(specials, size=(wl.T, wl.H)).astype(np.float32)
+    mix = rng.random(x32.shape) < 0.4
+    x32[mix] = rng.standard_normal(int(mix.sum())).astype(np.float32)
+    w = wl.topk_w.copy()
+    w[::3, 0] = 0.0
+    w[1::5, 1] = 1e-39          # denormal weight
+    w[2::7, 2] = -2.5
+    w[3::11, 3] = 3e38          # overflow to infinity in the chain
+    nan_rows = np.zeros_like(x32, bool)
+    nan_rows[5, 10] = nan_rows[17, 0] = True
+    x32[nan_rows] = np.nan
+    wl.topk_w = w
+    wl.x = x32 if yd == "f32" else synth.f32_to_bf16_bits(x32)
+    wl.x_dtype = wl.y_dtype = yd
+    wl.out_dtype = od
+    ctx = gu.make_context(wl)
+    try:
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        dev = gu.DeviceStep(ctx, wl)
+        dev.step()
+        dev.sync()
+        lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim, 0)
+        recv = oracle.pack(wl.x, lay["row_of"])
+        assert np.array_equal(gu.to_host(dev.recv, gu.NP_OF[yd]).view(np.uint8), recv.view(np.uint8))
+        chain = oracle.combine_chain32(recv, ODT[yd], wl.topk_w, lay["row_of"])
+        out = gu.to_host(dev.out, gu.NP_OF[od])
+        got32 = out if od == "f32" else synth.bf16_bits_to_f32(out)
+        want_nan = np.isnan(chain)
+        assert want_nan.any() and np.array_equal(np.isnan(got32), want_nan)
+        want_bits = chain.view(np.uint32) if od == "f32" else oracle.f32_to_bf16(chain)
+        got_bits = out.view(np.uint32) if od == "f32" else out
+        assert np.array_equal(got_bits[~want_nan], want_bits[~want_nan])
+        assert np.isinf(chain).any() and (np.abs(chain[np.isfinite(chain)]) < 1e-37).any()
+    finally:
+        ctx.destroy()
+
+
 def test_call_order_and_argument_errors():
     wl = synth.decode(T=64, H=256)
     ctx = gu.make_context(wl)
