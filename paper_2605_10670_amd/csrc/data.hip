@@ -391,7 +391,9 @@ hipError_t launch_combine(eep_ctx* c, const void* y, const float* w, void* out, 
 
 // ---------------------------------------------------------------------------
 // expert stand-ins (outside the measured path): one workgroup per receive row,
-// rows >= N (read from device memory) are skipped.
+// rows >= N (read from device memory) are skipped.  Same streaming access
+// policy as pack and combine: read-once loads are non-temporal, stores write
+// through.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_stub_copy(const u32x4* __restrict__ recv,
                                                    u32x4* __restrict__ y,
@@ -400,7 +402,8 @@ __global__ __launch_bounds__(256) void k_stub_copy(const u32x4* __restrict__ rec
   const int row = blockIdx.x;
   if (row >= status[0]) return;
   for (int v = threadIdx.x; v < row_vecs; v += blockDim.x)
-    y[(int64_t)row * row_vecs + v] = recv[(int64_t)row * row_vecs + v];
+    store_through(&y[(int64_t)row * row_vecs + v],
+                  __builtin_nontemporal_load(&recv[(int64_t)row * row_vecs + v]));
 }
 
 template <bool BF16>
@@ -413,14 +416,14 @@ __global__ __launch_bounds__(256) void k_stub_scale(
   const int e = p2l[slot_of[src_of[row]]];
   const float s = e >= 0 ? expert_scale[e] : 0.0f;
   for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) {
-    u32x4 d = recv[(int64_t)row * row_vecs + v];
+    u32x4 d = __builtin_nontemporal_load(&recv[(int64_t)row * row_vecs + v]);
     u32x4 o;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if constexpr (BF16) o[i] = pack_bf16x2(s * bf16_lo(d[i]), s * bf16_hi(d[i]));
       else o[i] = __float_as_uint(s * __uint_as_float(d[i]));
     }
-    y[(int64_t)row * row_vecs + v] = o;
+    store_through(&y[(int64_t)row * row_vecs + v], o);
   }
 }
 
@@ -434,7 +437,7 @@ __global__ __launch_bounds__(256) void k_stub_dequant(const u32x4* __restrict__ 
   const int row = blockIdx.x;
   if (row >= status[0]) return;
   for (int v = threadIdx.x; v < row_vecs; v += blockDim.x) {
-    u32x4 d = q[(int64_t)row * row_vecs + v];
+    u32x4 d = __builtin_nontemporal_load(&q[(int64_t)row * row_vecs + v]);
     float sc = scale[(int64_t)row * groups_per_row + (v * 16) / group];
     u32x4 o[2];
 #pragma unroll
@@ -446,8 +449,8 @@ __global__ __launch_bounds__(256) void k_stub_dequant(const u32x4* __restrict__ 
       o[i >> 1][(i & 1) * 2] = pack_bf16x2(f0, f1);
       o[i >> 1][(i & 1) * 2 + 1] = pack_bf16x2(f2, f3);
     }
-    y[((int64_t)row * row_vecs + v) * 2] = o[0];
-    y[((int64_t)row * row_vecs + v) * 2 + 1] = o[1];
+    store_through(&y[((int64_t)row * row_vecs + v) * 2], o[0]);
+    store_through(&y[((int64_t)row * row_vecs + v) * 2 + 1], o[1]);
   }
 }
 
