@@ -26,14 +26,13 @@
 //                workgroup; row = slot offset + pairs of earlier tiles + rank
 //                in tile.  Each workgroup repeats the small scan rather than
 //                wait for another kernel.
-//   k_scan + k_position  (> 64 tiles) the same scan done once by one
-//                workgroup, then a wide grid computes the rows.
+//   k_tile_prefix + k_position  (> 64 tiles) the tile prefixes are computed once
+//                by a few workgroups, then a wide grid computes the rows.
 #include "eep_internal.hpp"
 
 namespace eep {
 
 constexpr int kMapThreads = 1024;
-constexpr int kScanThreads = 1024;
 constexpr int kPosThreads = 256;
 
 // Tile b covers tokens [t0, t0 + ntok) of source rank b / tiles_per_rank; the
@@ -194,7 +193,8 @@ __device__ inline void block_exclusive_scan(const int32_t* s_count, int32_t* s_o
   __syncthreads();
 }
 
-// Per-step tables every consumer needs, written once by one workgroup.
+// Per-step tables every consumer needs, written once by one workgroup
+// (`count` may be null when another kernel has already written it).
 template <int NT>
 __device__ inline void write_step_tables(const int32_t* s_count, const int32_t* s_offset,
                                          int dropped_unc, int dropped_msk, int version,
@@ -206,7 +206,7 @@ __device__ inline void write_step_tables(const int32_t* s_count, const int32_t* 
   const int tid = threadIdx.x;
   for (int p = tid; p <= P; p += NT) {
     offset[p] = s_offset[p];
-    if (p < P) count[p] = s_count[p];
+    if (count != nullptr && p < P) count[p] = s_count[p];
   }
   for (int r = tid; r < R; r += NT) {
     rank_offset[r] = s_offset[r * S];
@@ -320,87 +320,133 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
 }
 
 // ---------------------------------------------------------------------------
-// Many tiles (> 64, the prefill regime): one workgroup scans, a wide grid
-// positions.  Thread = slot; it walks down the [tiles][P] count matrix keeping a
-// running sum and writes pre_tile[tile][slot] = pairs of the slot in earlier
-// tiles.  Loads are fetched kTileBatch rows at a time.
+// Many tiles (> 64, the prefill regime): three launches.
+//   k_tile_prefix  one workgroup per 64 slots (lane = slot, coalesced rows of the
+//                  [tiles][P] count matrix); its 16 wavefronts split the tiles,
+//                  each sums its share (one round of loads when the share is
+//                  <= 32 tiles), the shares are combined through LDS, and every
+//                  wavefront writes pre_tile[tile][slot] = pairs of the slot in
+//                  earlier tiles, plus the slot totals.
+//   k_position     a wide grid; every workgroup scans the P slot totals in LDS
+//                  (cheap, and it saves a launch), then row = slot offset +
+//                  earlier-tile pairs + rank in tile.  Workgroup 0 publishes the
+//                  per-step tables.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kScanThreads) void k_scan(
-    const int32_t* __restrict__ cnt_tile, const int32_t* __restrict__ blk_unc,
-    const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
-    int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
-    int32_t* __restrict__ rank_offset, int32_t* __restrict__ pre_tile,
-    int32_t* __restrict__ status, int32_t* __restrict__ step_epoch, int num_tiles, int R, int S,
-    int P) {
-  extern __shared__ int32_t smem[];
-  int32_t* s_count = smem;           // [P]
-  int32_t* s_offset = s_count + P;   // [P+1]
-  __shared__ int32_t s_wave[kScanThreads / 64];
-  __shared__ int32_t s_drop[2];
-  const int tid = threadIdx.x;
+constexpr int kPrefixThreads = 1024;
+constexpr int kPrefixWaves = kPrefixThreads / 64;
 
-  if (tid < 2) s_drop[tid] = 0;
-  int du = 0, dm = 0;
-  for (int b = tid; b < num_tiles; b += kScanThreads) {
-    du += blk_unc[b];
-    dm += blk_msk[b];
-  }
-  const int version = *tbl_version;
-  for (int p = tid; p < P; p += kScanThreads) {
-    int run = 0;
-    for (int tb = 0; tb < num_tiles; tb += kTileBatch) {
-      int v[kTileBatch];
+__global__ __launch_bounds__(kPrefixThreads) void k_tile_prefix(
+    const int32_t* __restrict__ cnt_tile, int32_t* __restrict__ pre_tile,
+    int32_t* __restrict__ count, int num_tiles, int tiles_per_wave, int P) {
+  __shared__ int32_t s_part[kPrefixWaves][64];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int p = blockIdx.x * 64 + lane;
+  const int b_lo = wave * tiles_per_wave;
+  int b_hi = b_lo + tiles_per_wave;
+  if (b_hi > num_tiles) b_hi = num_tiles;
+  const bool single = tiles_per_wave <= kTileBatch;  // the share fits one batch: keep it in registers
+  int v[kTileBatch];
+  int part = 0;
+  if (p < P) {
+    for (int tb = b_lo; tb < b_hi; tb += kTileBatch) {
 #pragma unroll
       for (int u = 0; u < kTileBatch; ++u)
-        v[u] = tb + u < num_tiles ? cnt_tile[(int64_t)(tb + u) * P + p] : 0;
+        v[u] = tb + u < b_hi ? cnt_tile[(int64_t)(tb + u) * P + p] : 0;
 #pragma unroll
-      for (int u = 0; u < kTileBatch; ++u) {
-        if (tb + u < num_tiles) pre_tile[(int64_t)(tb + u) * P + p] = run;
-        run += v[u];
-      }
+      for (int u = 0; u < kTileBatch; ++u) part += v[u];
     }
-    s_count[p] = run;
   }
+  s_part[wave][lane] = part;
   __syncthreads();
-  if (du) atomicAdd(&s_drop[0], du);  // zeroed before the barrier, read after the scan's barriers
-  if (dm) atomicAdd(&s_drop[1], dm);
-  block_exclusive_scan<kScanThreads>(s_count, s_offset, s_wave, P);
-  write_step_tables<kScanThreads>(s_count, s_offset, s_drop[0], s_drop[1], version, count, offset,
-                                  rank_count, rank_offset, status, step_epoch, R, S, P);
+  if (p >= P) return;
+  int run = 0;
+  for (int w = 0; w < wave; ++w) run += s_part[w][lane];
+  if (wave == 0) {
+    int total = 0;
+    for (int w = 0; w < kPrefixWaves; ++w) total += s_part[w][lane];
+    count[p] = total;
+  }
+  for (int tb = b_lo; tb < b_hi; tb += kTileBatch) {
+    if (!single) {
+#pragma unroll
+      for (int u = 0; u < kTileBatch; ++u)
+        v[u] = tb + u < b_hi ? cnt_tile[(int64_t)(tb + u) * P + p] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < kTileBatch; ++u) {
+      if (tb + u < b_hi) pre_tile[(int64_t)(tb + u) * P + p] = run;
+      run += v[u];
+    }
+  }
 }
 
 template <int KC>
 __global__ __launch_bounds__(kPosThreads) void k_position(
     const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pre_tile,
-    const int32_t* __restrict__ offset, const int32_t* __restrict__ status,
+    const int32_t* __restrict__ count_in, const int32_t* __restrict__ blk_unc,
+    const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
     int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int32_t* __restrict__ cnt_src,
-    int k_rt, int tokens_per_rank, int tiles_per_rank, int tile_tokens, int num_tiles,
-    int total_pairs, int R, int P) {
+    int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
+    int32_t* __restrict__ rank_offset, int32_t* __restrict__ status,
+    int32_t* __restrict__ step_epoch, int k_rt, int tokens_per_rank, int tiles_per_rank,
+    int tile_tokens, int num_tiles, int total_pairs, int R, int S, int P) {
   const int k = KC > 0 ? KC : k_rt;
-  const int g = blockIdx.x * kPosThreads + threadIdx.x;
+  extern __shared__ int32_t smem[];
+  int32_t* s_count = smem;           // [P]
+  int32_t* s_offset = s_count + P;   // [P+1]
+  __shared__ int32_t s_wave[kPosThreads / 64];
+  __shared__ int32_t s_drop[2];
+  const int tid = threadIdx.x;
+  const int g = blockIdx.x * kPosThreads + tid;
+
+  // this thread's pair, fetched together with the slot totals
+  int p = -1, rank_in_tile = 0;
+  if (g < total_pairs) {
+    p = slot_of[g];
+    rank_in_tile = row_of[g];
+  }
+  for (int q = tid; q < P; q += kPosThreads) s_count[q] = count_in[q];
+  int du = 0, dm = 0, version = 0;
+  if (blockIdx.x == 0) {
+    for (int b = tid; b < num_tiles; b += kPosThreads) {
+      du += blk_unc[b];
+      dm += blk_msk[b];
+    }
+    if (tid == 0) version = *tbl_version;
+  }
+  if (tid < 2) s_drop[tid] = 0;
+  __syncthreads();
+  if (du) atomicAdd(&s_drop[0], du);
+  if (dm) atomicAdd(&s_drop[1], dm);
+  block_exclusive_scan<kPosThreads>(s_count, s_offset, s_wave, P);
+
   // pairs per (source rank, slot): difference of the tile prefixes at the source
   // rank's first tile and at the next source rank's first tile
   for (int i = g; i < R * P; i += gridDim.x * kPosThreads) {
     int bs = i / P;
-    int p = i - bs * P;
+    int q = i - bs * P;
     int first = bs * tiles_per_rank, next = first + tiles_per_rank;
-    int lo_v = pre_tile[(int64_t)first * P + p];
-    int hi_v = next < num_tiles ? pre_tile[(int64_t)next * P + p] : offset[p + 1] - offset[p];
+    int lo_v = pre_tile[(int64_t)first * P + q];
+    int hi_v = next < num_tiles ? pre_tile[(int64_t)next * P + q] : s_count[q];
     cnt_src[i] = hi_v - lo_v;
   }
-  if (g >= total_pairs) return;
-  const int t = g / k;
-  const int src_rank = t / tokens_per_rank;
-  const int tile = src_rank * tiles_per_rank + (t - src_rank * tokens_per_rank) / tile_tokens;
-  const int N = status[0];
-  int p = slot_of[g];
-  int row = -1;
-  if (p >= 0) {
-    row = offset[p] + pre_tile[(int64_t)tile * P + p] + row_of[g];  // row_of: rank in tile
-    src_of[row] = g;
+  if (g < total_pairs) {
+    const int t = g / k;
+    const int src_rank = t / tokens_per_rank;
+    const int tile = src_rank * tiles_per_rank + (t - src_rank * tokens_per_rank) / tile_tokens;
+    const int N = s_offset[P];
+    int row = -1;
+    if (p >= 0) {
+      row = s_offset[p] + pre_tile[(int64_t)tile * P + p] + rank_in_tile;
+      src_of[row] = g;
+    }
+    row_of[g] = row;
+    if (g >= N) src_of[g] = -1;  // rows past the last routed pair
   }
-  row_of[g] = row;
-  if (g >= N) src_of[g] = -1;  // rows past the last routed pair
+  if (blockIdx.x == 0)
+    write_step_tables<kPosThreads>(s_count, s_offset, s_drop[0], s_drop[1], version, nullptr,
+                                   offset, rank_count, rank_offset, status, step_epoch, R, S, P);
 }
 
 // T == 0: nothing is routed; publish empty tables.
@@ -455,19 +501,20 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
                        c->S, c->P);
     return hipGetLastError();
   }
-  size_t lds_scan = sizeof(int32_t) * ((size_t)2 * c->P + 1);
-  hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanThreads), lds_scan, st, c->cnt_tile, c->blk_unc,
-                     c->blk_msk, c->tbl_version, c->count, c->offset, c->rank_count,
-                     c->rank_offset, c->base_tile, c->status, c->step_epoch, g.num_tiles, c->R, c->S,
-                     c->P);
+  int tiles_per_wave = (g.num_tiles + kPrefixWaves - 1) / kPrefixWaves;
+  hipLaunchKernelGGL(k_tile_prefix, dim3((c->P + 63) / 64), dim3(kPrefixThreads), 0, st,
+                     c->cnt_tile, c->base_tile, c->count, g.num_tiles, tiles_per_wave, c->P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   int total_pairs = T * c->k;
+  size_t lds_pos = sizeof(int32_t) * ((size_t)2 * c->P + 1);
   auto kern = k8 ? k_position<8> : k_position<0>;
   hipLaunchKernelGGL(kern, dim3((total_pairs + kPosThreads - 1) / kPosThreads), dim3(kPosThreads),
-                     0, st, c->slot_of, c->base_tile, c->offset, c->status, c->row_of, c->src_of,
-                     c->cnt_src, c->k, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens,
-                     g.num_tiles, total_pairs, c->R, c->P);
+                     lds_pos, st, c->slot_of, c->base_tile, c->count, c->blk_unc, c->blk_msk,
+                     c->tbl_version, c->row_of, c->src_of, c->cnt_src, c->offset, c->rank_count,
+                     c->rank_offset, c->status, c->step_epoch, c->k,
+                     g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, g.num_tiles, total_pairs,
+                     c->R, c->S, c->P);
   return hipGetLastError();
 }
 
