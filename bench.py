@@ -259,6 +259,16 @@ def main():
     stream.synchronize()
     stage_ms = {name: sum(e[i].elapsed_time(e[i + 1]) for e in ev) / len(ev)
                 for i, name in enumerate(("layout", "dispatch", "combine"))}
+    # what two consecutive event records measure with no kernel between them: an upper bound
+    # of the part of every stage figure above that is event machinery, not kernel time (the
+    # stage figures are reported as measured, i.e. slightly above the profiler's kernel times)
+    gap_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    for e in gap_ev:
+        combine()
+        e[0].record(stream)
+        e[1].record(stream)
+    stream.synchronize()
+    event_gap_ms = sum(e[0].elapsed_time(e[1]) for e in gap_ev) / len(gap_ev)
     per_step = sorted(e[0].elapsed_time(e[3]) * 1e3 for e in ev)
     pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     other_ms = time_events(stream, step, args.steps)   # eager steps, no inner events
@@ -293,6 +303,7 @@ def main():
         "copy_ceiling_gbs": copy_gbs,
         "frac_of_copy_ceiling": nbytes["total"] / (ms * 1e-3) / 1e9 / copy_gbs,
         "stages_us": {n: v * 1e3 for n, v in stage_ms.items()},
+        "event_gap_us": event_gap_ms * 1e3,
         "eager_us_per_step": other_ms * 1e3,
         "eager_step_with_events_us": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved"],
