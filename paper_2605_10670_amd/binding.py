@@ -95,6 +95,11 @@ def load():
     return lib
 
 
+def _library():
+    """`load` under a name that arguments called `load` cannot shadow."""
+    return load()
+
+
 def _strerror(code):
     return load().eep_strerror(code).decode()
 
@@ -168,17 +173,13 @@ def plan_repair(cur_p2l, active, R, S, S_prim, E, load=None):
     ld = None if load is None else np.ascontiguousarray(load, np.float32)
     new, kind, src = (np.empty(R * S, np.int32) for _ in range(3))
     summary = np.zeros(4, np.int32)
-    rc = load_lib_plan(R, S, S_prim, E, cur, act, ld, new, kind, src, summary)
+    rc = _library().eep_plan_repair(R, S, S_prim, E, cur.ctypes.data, act.ctypes.data,
+                                None if ld is None else ld.ctypes.data, new.ctypes.data,
+                                kind.ctypes.data, src.ctypes.data, summary.ctypes.data)
     if rc not in (OK, ERR_COVERAGE):
         _check(rc, "eep_plan_repair")
     return dict(p2l=new, kind=kind, src_slot=src, local=int(summary[0]), peer=int(summary[1]),
                 dram=int(summary[2]), unplaced=int(summary[3]))
-
-
-def load_lib_plan(R, S, S_prim, E, cur, act, ld, new, kind, src, summary):
-    return load().eep_plan_repair(R, S, S_prim, E, cur.ctypes.data, act.ctypes.data,
-                                  None if ld is None else ld.ctypes.data, new.ctypes.data,
-                                  kind.ctypes.data, src.ctypes.data, summary.ctypes.data)
 
 
 class Graph:
