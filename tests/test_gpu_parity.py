@@ -214,6 +214,31 @@ def test_random_configurations(oracle, seed):
     assert got["rank_count"][dead].sum() == 0
 
 
+def test_large_tables_near_the_lds_limit(oracle):
+    """1024 slots and 1024 logical experts: the map kernel's LDS tables take ~41 KB
+    and the scan walks 1024 slots per workgroup; a shape whose tables cannot fit
+    is refused at create time."""
+    rng = np.random.default_rng(77)
+    R, sp, sr, k, T, H = 64, 14, 2, 8, 64 * 64, 64
+    E = R * sp + 128                      # more experts than primary slots: some live only in
+    S = sp + sr                           # redundant slots, some are uncovered
+    p2l = np.full(R * S, -1, np.int32)
+    p2l[:] = rng.permutation(np.concatenate([np.arange(E), rng.integers(0, E, R * S - E)]))[:R * S] \
+        if R * S >= E else rng.integers(0, E, R * S)
+    active = synth.active_mask(R, (5, 40))
+    x = synth.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    wl = synth.Workload("large-tables", T, H, E, k, R, sp, sr, "bf16", "bf16", "bf16", "identity",
+                        (5, 40), idx, w, x, p2l, active)
+    got, _ = run_and_compare(oracle, wl, strict=False)
+    assert got["rank_count"][[5, 40]].sum() == 0
+    assert got["N"] + got["n_uncovered"] == T * k
+    with pytest.raises(binding.EepError) as ei:
+        binding.Context(num_ranks=512, slots_per_rank=32, primary_slots=16, num_logical=4096,
+                        max_tokens=512, topk=8, hidden=64)
+    assert ei.value.code == binding.ERR_INVALID_ARG
+
+
 def test_prefill_fp8_reduced(oracle):
     wl = synth.prefill_fp8(T=1024, H=1024)
     got, _ = run_and_compare(oracle, wl)
