@@ -96,7 +96,20 @@ typedef struct eep_ctx eep_ctx;
  * On error *out is NULL. */
 int eep_create(const eep_config* cfg, eep_ctx** out);
 
-/* Waits for the device, frees everything the context owns.  NULL is OK. */
+/* A further context of the SAME EP instance as `parent`: it shares parent's
+ * membership (the `active` mask -- one peer table per instance, Sec. 4.1) and has
+ * its own placement tables, layout arrays and shapes.  This is how the MoE
+ * layers of one model are set up: every layer has its own expert-location
+ * metadata (Sec. 5.1) while a rank failure concerns all of them at once.
+ * cfg->num_ranks must equal the parent's.  eep_set_membership through any
+ * context of the instance updates the one shared mask (and checks the coverage
+ * of every context that asked for strict_coverage); a rank dropped by one
+ * context's failure detection is dropped for all.  Attached contexts must be
+ * destroyed before the context that eep_create made. */
+int eep_create_attached(const eep_config* cfg, eep_ctx* parent, eep_ctx** out);
+
+/* Waits for the device, frees everything the context owns.  NULL is OK.
+ * EEP_ERR_STATE if attached contexts of this instance still exist. */
 int eep_destroy(eep_ctx* ctx);
 
 /* ---- table updates: between steps, stream-ordered (Sec. 3.1: repair and
@@ -215,7 +228,9 @@ int eep_read_failures(eep_ctx* ctx, int32_t* failed_host, void* stream);
  *   count[P], offset[P+1]          pairs per slot, exclusive prefix sum
  *   rank_count[R], rank_offset[R+1]
  *   cnt_src[R,P]                   pairs per (source rank, slot)
- *   status[4]                      {N, n_uncovered, n_masked, table version} */
+ *   status[4]                      {N, n_uncovered, n_masked, table version}
+ *                                  (version = placement updates of this context
+ *                                  + membership updates of the instance) */
 typedef struct {
   const int32_t *active, *phys_to_logical, *l2p_off, *l2p_list;
   const int32_t *slot_of, *row_of, *src_of;

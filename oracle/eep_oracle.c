@@ -25,7 +25,7 @@
  *   combine     Sec. 4.1: reduce the expert outputs per token, weighted by the
  *               router weights (Sec. 2.1).
  *
- * Readings where the paper is silent (same list as the design notes):
+ * Readings where the paper is silent:
  *   - canonical replica order: primary slots first, then ascending slot id;
  *   - selection: FIRST_LIVE (sel = 0) or SPREAD (sel = t mod n_live);
  *   - an index outside [0,E), or one that repeats an earlier index of the

@@ -59,6 +59,7 @@ def load():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     sig = {
         "eep_create": [ctypes.POINTER(_Config), ctypes.POINTER(vp)],
+        "eep_create_attached": [ctypes.POINTER(_Config), vp, ctypes.POINTER(vp)],
         "eep_destroy": [vp],
         "eep_set_membership": [vp, vp, vp],
         "eep_update_placement": [vp, vp, vp],
@@ -205,7 +206,7 @@ class Context:
 
     def __init__(self, *, num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk,
                  hidden, x_dtype="bf16", y_dtype="bf16", out_dtype="bf16", scale_group=None,
-                 policy=SPREAD, strict_coverage=True):
+                 policy=SPREAD, strict_coverage=True, parent=None):
         xd = DTYPES[x_dtype] if isinstance(x_dtype, str) else x_dtype
         if scale_group is None:
             scale_group = 128 if xd == FP8_E4M3 else 0
@@ -214,7 +215,12 @@ class Context:
                            DTYPES[out_dtype] if isinstance(out_dtype, str) else out_dtype,
                            scale_group, policy, 1 if strict_coverage else 0)
         self._h = ctypes.c_void_p()
-        _check(load().eep_create(ctypes.byref(self.cfg), ctypes.byref(self._h)), "eep_create")
+        self._parent = parent      # keeps the instance's first context alive
+        if parent is None:
+            _check(load().eep_create(ctypes.byref(self.cfg), ctypes.byref(self._h)), "eep_create")
+        else:   # same EP instance: shared membership, own placement and layout
+            _check(load().eep_create_attached(ctypes.byref(self.cfg), parent._h,
+                                              ctypes.byref(self._h)), "eep_create_attached")
         self.R, self.S, self.E, self.k = num_ranks, slots_per_rank, num_logical, topk
         self.P = num_ranks * slots_per_rank
         self.T_max = max_tokens
@@ -315,7 +321,7 @@ class Context:
 
     def destroy(self):
         if self._h:
-            load().eep_destroy(self._h)
+            _check(load().eep_destroy(self._h), "eep_destroy")
             self._h = ctypes.c_void_p()
 
     def __del__(self):

@@ -33,10 +33,15 @@ const char* eep_strerror(int code) {
 
 int eep_last_hip_error(eep_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
 
-int eep_create(const eep_config* cfg, eep_ctx** out) {
+}  // extern "C"
+
+namespace {
+
+int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   if (!out) return EEP_ERR_INVALID_ARG;
   *out = nullptr;
   if (!cfg) return EEP_ERR_INVALID_ARG;
+  if (parent && cfg->num_ranks != parent->R) return EEP_ERR_INVALID_ARG;
   const eep_config& f = *cfg;
   if (f.num_ranks < 1 || f.slots_per_rank < 1 || f.primary_slots < 0 ||
       f.primary_slots > f.slots_per_rank || f.num_logical < 1 || f.max_tokens < 0 || f.topk < 1 ||
@@ -92,6 +97,7 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
 
   hipError_t e = hipGetDevice(&c->device);
   if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
+  if (parent && parent->device != c->device) { delete c; return EEP_ERR_INVALID_ARG; }
 
   const int64_t pairs = (int64_t)c->T_max * c->k;
   int64_t* n = c->field_ints;
@@ -109,14 +115,14 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   n[EEP_V_CNT_SRC] = (int64_t)c->R * c->P;
   n[EEP_V_STATUS] = 4;
   int32_t** field_ptr[EEP_V_NUM_FIELDS] = {
-      &c->active, &c->p2l,   &c->l2p_off, &c->l2p_list,   &c->slot_of,     &c->row_of, &c->src_of,
+      &c->own_active, &c->p2l,   &c->l2p_off, &c->l2p_list,   &c->slot_of,     &c->row_of, &c->src_of,
       &c->count,  &c->offset, &c->rank_count, &c->rank_offset, &c->cnt_src, &c->status};
   // carve one slab; every array starts on a 256-byte boundary
   auto round_up = [](int64_t ints) { return (ints + 63) / 64 * 64; };
   int64_t total = 0;
   for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) total += round_up(n[i] > 0 ? n[i] : 1);
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
-  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 2 * round_up(1) +
+  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 3 * round_up(1) +
            3 * round_up(c->R);
   e = hipMalloc(&c->slab, (size_t)total * sizeof(int32_t));
   if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
@@ -130,6 +136,7 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   c->blk_unc = cur;   cur += round_up(c->max_tiles);
   c->blk_msk = cur;   cur += round_up(c->max_tiles);
   c->tbl_version = cur; cur += round_up(1);
+  c->mem_version_word = cur; cur += round_up(1);
   c->step_epoch = cur;  cur += round_up(1);
   c->signal = cur;      cur += round_up(c->R);
   c->withhold = cur;    cur += round_up(c->R);
@@ -137,12 +144,24 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   c->detect_timeout_ticks = 0;
   c->wall_clock_khz = 0;
 
-  // initial state: every rank live, every slot empty, nothing laid out
-  c->h_active.assign(c->R, 1);
+  // membership: a new instance (all ranks live), or the parent's
+  if (parent) {
+    c->mem = parent->mem;
+  } else {
+    c->mem = new (std::nothrow) eep_membership();
+    if (!c->mem) { (void)hipFree(c->slab); delete c; return EEP_ERR_INVALID_ARG; }
+    c->mem->R = c->R;
+    c->mem->active = c->own_active;
+    c->mem->mem_version = c->mem_version_word;
+    c->mem->h_active.assign(c->R, 1);
+    c->mem->version = 0;
+  }
+  c->active = c->mem->active;
+  // initial state: every slot empty, nothing laid out
   c->h_p2l.assign(c->P, -1);
   hipStream_t st = nullptr;
   e = hipMemsetAsync(c->slab, 0, (size_t)total * sizeof(int32_t), st);
-  if (e == hipSuccess) e = launch_fill(c->active, 1, c->R, st);
+  if (e == hipSuccess) e = launch_fill(c->own_active, 1, c->R, st);
   if (e == hipSuccess) e = launch_fill(c->p2l, -1, c->P, st);
   if (e == hipSuccess) e = launch_fill(c->l2p_list, -1, c->P, st);
   if (e == hipSuccess) e = launch_fill(c->slot_of, -1, pairs, st);
@@ -151,32 +170,62 @@ int eep_create(const eep_config* cfg, eep_ctx** out) {
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
     (void)hipFree(c->slab);
+    if (!parent) delete c->mem;
     delete c;
     return EEP_ERR_HIP;
   }
+  c->mem->members.push_back(c);
   *out = c;
   return EEP_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int eep_create(const eep_config* cfg, eep_ctx** out) { return create_impl(cfg, nullptr, out); }
+
+int eep_create_attached(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
+  if (!parent) {
+    if (out) *out = nullptr;
+    return EEP_ERR_INVALID_ARG;
+  }
+  return create_impl(cfg, parent, out);
+}
+
 int eep_destroy(eep_ctx* ctx) {
   if (!ctx) return EEP_OK;
+  eep_membership* m = ctx->mem;
+  const bool is_root = m->members.front() == ctx;
+  if (is_root && m->members.size() > 1) return EEP_ERR_STATE;  // attached contexts go first
   hipError_t e = hipDeviceSynchronize();
+  for (size_t i = 0; i < m->members.size(); ++i)
+    if (m->members[i] == ctx) {
+      m->members.erase(m->members.begin() + i);
+      break;
+    }
   hipError_t e2 = hipFree(ctx->slab);
+  if (is_root) delete m;
   delete ctx;
   return (e == hipSuccess && e2 == hipSuccess) ? EEP_OK : EEP_ERR_HIP;
 }
 
 int eep_set_membership(eep_ctx* c, const int32_t* active_host, void* stream) {
   if (!c || !active_host) return EEP_ERR_INVALID_ARG;
+  eep_membership* m = c->mem;
   std::vector<int32_t> a(c->R);
   for (int r = 0; r < c->R; ++r) a[r] = active_host[r] != 0 ? 1 : 0;
-  if (c->cfg.strict_coverage && host_uncovered_experts(c->P, c->E, c->S, c->h_p2l.data(), a.data()) > 0)
-    return EEP_ERR_COVERAGE;
-  hipError_t e = launch_patch(c->active, a.data(), c->R, c->tbl_version, c->version + 1,
+  // the mask is shared: every context of the instance that asked for strict
+  // coverage must stay covered under its own placement
+  for (eep_ctx* o : m->members)
+    if (o->cfg.strict_coverage &&
+        host_uncovered_experts(o->P, o->E, o->S, o->h_p2l.data(), a.data()) > 0)
+      return EEP_ERR_COVERAGE;
+  hipError_t e = launch_patch(m->active, a.data(), c->R, m->mem_version, m->version + 1,
                               (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e);
-  c->h_active = a;
-  c->version += 1;
+  m->h_active = a;
+  m->version += 1;
   return EEP_OK;
 }
 
@@ -184,7 +233,7 @@ int eep_update_placement(eep_ctx* c, const int32_t* p2l_host, void* stream) {
   if (!c || !p2l_host) return EEP_ERR_INVALID_ARG;
   for (int p = 0; p < c->P; ++p)
     if (p2l_host[p] < -1 || p2l_host[p] >= c->E) return EEP_ERR_INVALID_ARG;
-  if (c->cfg.strict_coverage && host_uncovered_experts(c->P, c->E, c->S, p2l_host, c->h_active.data()) > 0)
+  if (c->cfg.strict_coverage && host_uncovered_experts(c->P, c->E, c->S, p2l_host, c->mem->h_active.data()) > 0)
     return EEP_ERR_COVERAGE;
   std::vector<int32_t> off(c->E + 1), list(c->P);
   host_replica_lists(c->P, c->E, c->S, c->S_prim, p2l_host, off.data(), list.data());
@@ -322,7 +371,7 @@ int eep_read_failures(eep_ctx* c, int32_t* failed_host, void* stream) {
   for (int r = 0; r < c->R; ++r) {
     failed_host[r] = failed_host[r] != 0;
     if (failed_host[r]) {
-      c->h_active[r] = 0;  // the kernel already cleared the device copy
+      c->mem->h_active[r] = 0;  // the kernel already cleared the device copy
       any = true;
     }
   }

@@ -49,8 +49,21 @@ struct PatchChunk {
 
 }  // namespace eep
 
+// The membership of one EP instance (the peer table's `active` column, Fig. 7):
+// one device array and one host copy, shared by every context of the instance.
+// It lives in the slab of the context that created it (the "root").
+struct eep_membership {
+  int R;
+  int32_t* active;       // device [R]
+  int32_t* mem_version;  // device word: number of membership updates
+  std::vector<int32_t> h_active;
+  int32_t version;
+  std::vector<eep_ctx*> members;  // root first
+};
+
 struct eep_ctx {
   eep_config cfg;
+  eep_membership* mem;  // shared; owned by the root context
   int R, S, S_prim, P, E, k, H, T_max;
   int64_t x_row_bytes, y_row_bytes, out_row_bytes, scale_row_bytes;
   int device;
@@ -58,7 +71,9 @@ struct eep_ctx {
 
   void* slab;  // the one device allocation everything below points into
   // tables (fixed addresses, contents patched in place)
-  int32_t *active, *p2l, *l2p_off, *l2p_list, *tbl_version;
+  int32_t *active;  // == mem->active
+  int32_t *own_active, *mem_version_word;  // slab space used only when this context is the root
+  int32_t *p2l, *l2p_off, *l2p_list, *tbl_version;  // tbl_version: placement updates of this context
   // per-step layout results
   int32_t *slot_of, *row_of, *src_of, *count, *offset, *rank_count, *rank_offset, *cnt_src, *status;
   // per-step scratch
@@ -71,8 +86,8 @@ struct eep_ctx {
   int wall_clock_khz;
 
   // host shadows of the tables (coverage is validated without touching the GPU)
-  std::vector<int32_t> h_active, h_p2l;
-  int32_t version;
+  std::vector<int32_t> h_p2l;
+  int32_t version;  // placement updates of this context
   int layout_T;  // T of the last dispatch_layout, -1 if none yet
   int last_hip_error;
   int64_t field_ints[EEP_V_NUM_FIELDS];

@@ -237,7 +237,8 @@ template <int KC>
 __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
     const int32_t* __restrict__ cnt_tile, const int32_t* __restrict__ blk_unc,
     const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
-    const int32_t* __restrict__ slot_of, int32_t* __restrict__ row_of,
+    const int32_t* __restrict__ mem_version, const int32_t* __restrict__ slot_of,
+    int32_t* __restrict__ row_of,
     int32_t* __restrict__ src_of, int32_t* __restrict__ count, int32_t* __restrict__ offset,
     int32_t* __restrict__ rank_count, int32_t* __restrict__ rank_offset,
     int32_t* __restrict__ cnt_src, int32_t* __restrict__ status,
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
       du += blk_unc[i];
       dm += blk_msk[i];
     }
-    if (tid == 0) version = *tbl_version;
+    if (tid == 0) version = *tbl_version + *mem_version;
   }
   if (tid < 2) s_drop[tid] = 0;
   for (int p = tid; p < P; p += kFusedThreads) {
@@ -386,7 +387,8 @@ __global__ __launch_bounds__(kPosThreads) void k_position(
     const int32_t* __restrict__ slot_of, const int32_t* __restrict__ pre_tile,
     const int32_t* __restrict__ count_in, const int32_t* __restrict__ blk_unc,
     const int32_t* __restrict__ blk_msk, const int32_t* __restrict__ tbl_version,
-    int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int32_t* __restrict__ cnt_src,
+    const int32_t* __restrict__ mem_version, int32_t* __restrict__ row_of,
+    int32_t* __restrict__ src_of, int32_t* __restrict__ cnt_src,
     int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
     int32_t* __restrict__ rank_offset, int32_t* __restrict__ status,
     int32_t* __restrict__ step_epoch, int k_rt, int tokens_per_rank, int tiles_per_rank,
@@ -413,7 +415,7 @@ __global__ __launch_bounds__(kPosThreads) void k_position(
       du += blk_unc[b];
       dm += blk_msk[b];
     }
-    if (tid == 0) version = *tbl_version;
+    if (tid == 0) version = *tbl_version + *mem_version;
   }
   if (tid < 2) s_drop[tid] = 0;
   __syncthreads();
@@ -451,8 +453,8 @@ __global__ __launch_bounds__(kPosThreads) void k_position(
 
 // T == 0: nothing is routed; publish empty tables.
 __global__ __launch_bounds__(256) void k_empty_step(
-    const int32_t* __restrict__ tbl_version, int32_t* __restrict__ count,
-    int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
+    const int32_t* __restrict__ tbl_version, const int32_t* __restrict__ mem_version,
+    int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ rank_count,
     int32_t* __restrict__ rank_offset, int32_t* __restrict__ cnt_src,
     int32_t* __restrict__ status, int32_t* __restrict__ step_epoch, int R, int P) {
   for (int p = threadIdx.x; p <= P; p += 256) {
@@ -466,7 +468,7 @@ __global__ __launch_bounds__(256) void k_empty_step(
   for (int i = threadIdx.x; i < R * P; i += 256) cnt_src[i] = 0;
   if (threadIdx.x == 0) {
     status[0] = status[1] = status[2] = 0;
-    status[3] = *tbl_version;
+    status[3] = *tbl_version + *mem_version;
     *step_epoch = *step_epoch + 1;
   }
 }
@@ -475,7 +477,8 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
   Tiling g = make_tiling(T, c->R);
   const bool k8 = c->k == 8;
   if (g.num_tiles == 0) {
-    hipLaunchKernelGGL(k_empty_step, dim3(1), dim3(256), 0, st, c->tbl_version, c->count,
+    hipLaunchKernelGGL(k_empty_step, dim3(1), dim3(256), 0, st, c->tbl_version,
+                       c->mem->mem_version, c->count,
                        c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
                        c->step_epoch, c->R, c->P);
     return hipGetLastError();
@@ -495,7 +498,8 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
     size_t lds = sizeof(int32_t) * ((size_t)3 * c->P + 1);
     auto kern = k8 ? k_scan_position<8> : k_scan_position<0>;
     hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kFusedThreads), lds, st, c->cnt_tile,
-                       c->blk_unc, c->blk_msk, c->tbl_version, c->slot_of, c->row_of, c->src_of,
+                       c->blk_unc, c->blk_msk, c->tbl_version, c->mem->mem_version, c->slot_of, c->row_of,
+                       c->src_of,
                        c->count, c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
                        c->step_epoch, c->k, g.num_tiles, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, c->R,
                        c->S, c->P);
@@ -511,7 +515,8 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
   auto kern = k8 ? k_position<8> : k_position<0>;
   hipLaunchKernelGGL(kern, dim3((total_pairs + kPosThreads - 1) / kPosThreads), dim3(kPosThreads),
                      lds_pos, st, c->slot_of, c->base_tile, c->count, c->blk_unc, c->blk_msk,
-                     c->tbl_version, c->row_of, c->src_of, c->cnt_src, c->offset, c->rank_count,
+                     c->tbl_version, c->mem->mem_version, c->row_of, c->src_of, c->cnt_src, c->offset,
+                     c->rank_count,
                      c->rank_offset, c->status, c->step_epoch, c->k,
                      g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, g.num_tiles, total_pairs,
                      c->R, c->S, c->P);
