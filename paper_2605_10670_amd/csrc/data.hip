@@ -110,12 +110,16 @@ hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* re
   if (row_vecs % 64 == 0) {
     // the largest pass width <= kPackVecs that divides the row
     const int per_lane = row_vecs / 64;
-    if (per_lane % 14 == 0) return launch_pack_t<14, true>(c, x, x_scale, recv_x, recv_scale, T, st);
-    if (per_lane % 8 == 0) return launch_pack_t<8, true>(c, x, x_scale, recv_x, recv_scale, T, st);
-    if (per_lane % 7 == 0) return launch_pack_t<7, true>(c, x, x_scale, recv_x, recv_scale, T, st);
-    if (per_lane % 4 == 0) return launch_pack_t<4, true>(c, x, x_scale, recv_x, recv_scale, T, st);
-    if (per_lane % 2 == 0) return launch_pack_t<2, true>(c, x, x_scale, recv_x, recv_scale, T, st);
-    return launch_pack_t<1, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+    int u = kPackVecs;
+    while (per_lane % u != 0) --u;
+    switch (u) {
+#define EEP_PACK_CASE(U) \
+  case U: return launch_pack_t<U, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+      EEP_PACK_CASE(14) EEP_PACK_CASE(13) EEP_PACK_CASE(12) EEP_PACK_CASE(11) EEP_PACK_CASE(10)
+      EEP_PACK_CASE(9) EEP_PACK_CASE(8) EEP_PACK_CASE(7) EEP_PACK_CASE(6) EEP_PACK_CASE(5)
+      EEP_PACK_CASE(4) EEP_PACK_CASE(3) EEP_PACK_CASE(2) EEP_PACK_CASE(1)
+#undef EEP_PACK_CASE
+    }
   }
   return launch_pack_t<kPackVecs, false>(c, x, x_scale, recv_x, recv_scale, T, st);
 }
@@ -381,6 +385,7 @@ static hipError_t launch_combine_t(eep_ctx* c, const void* y, const float* w, vo
                                    hipStream_t st) {
   int row_vecs = (int)(c->y_row_bytes / 16);
   int parts = (row_vecs + 64 * kCombineCols - 1) / (64 * kCombineCols);
+  if ((int64_t)T * parts > 0x7fffffffLL) return hipErrorInvalidValue;  // grid size limit
   dim3 grid((unsigned)((int64_t)T * parts)), block(64);
   if (c->k == 8)
     hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 8>), grid, block, 0, st, (const u32x4*)y, w,

@@ -165,6 +165,8 @@ def test_dtype_and_topk_matrix(oracle, dtypes, k):
     dict(R=4, sp=4, sr=1, k=3, T=4 * 50, H=8192, xd="bf16"),       # 16 KiB rows: two pack passes
     dict(R=4, sp=4, sr=1, k=5, T=4 * 7, H=5000, xd="f32"),         # 20000-byte fp32 rows, ragged parts
     dict(R=2, sp=1, sr=3, k=2, T=2 * 300, H=8, xd="bf16"),         # 16-byte rows, more replicas than experts
+    dict(R=4, sp=2, sr=1, k=4, T=4 * 33, H=4608, xd="bf16"),       # 9 vectors per lane (pass width 9)
+    dict(R=4, sp=2, sr=1, k=4, T=4 * 20, H=11264, xd="bf16"),      # 22 per lane: two passes of 11
 ])
 def test_wide_and_odd_shapes(oracle, shape):
     R, sp, sr, k, T, H, xd = (shape[n] for n in ("R", "sp", "sr", "k", "T", "H", "xd"))
