@@ -65,3 +65,37 @@ def plan_repair(cur, active, R, S, S_prim, E, load=None):
         now[p], kind[p], src[p] = e, PEER, peers[0]
     return dict(p2l=now, kind=kind, src_slot=src, local=kind.count(LOCAL), peer=kind.count(PEER),
                 dram=kind.count(DRAM), unplaced=unplaced)
+
+
+# outcome per slot of carry_out_repair
+UNTOUCHED, FROM_PEER, FROM_DRAM, FROM_DRAM_FALLBACK, SKIPPED = 0, 1, 2, 3, 4
+
+
+def carry_out_repair(weights, backup, new_p2l, kind, src_slot, active_now, S):
+    """Weight movement that satisfies a planned placement (Sec. 3.5's source
+    hierarchy; Sec. 5.1: the active mask is looked up when a transfer is issued,
+    and an expert whose planned source rank has gone inactive since the plan was
+    made is filled from the DRAM backup instead).
+
+    weights: list of P byte strings (what each slot holds now); backup: list of E
+    byte strings.  Slots planned as already-local or empty are not touched; a
+    destination on a rank that is no longer active is skipped.  Every transfer
+    reads the state before the batch (a source is never also a destination).
+    Returns (new weights, outcome per slot).
+    """
+    P = len(weights)
+    after = list(weights)
+    outcome = [UNTOUCHED] * P
+    for p in range(P):
+        if kind[p] != PEER and kind[p] != DRAM:
+            continue
+        if not active_now[p // S]:
+            outcome[p] = SKIPPED
+            continue
+        if kind[p] == PEER and active_now[src_slot[p] // S]:
+            after[p] = weights[src_slot[p]]
+            outcome[p] = FROM_PEER
+        else:
+            after[p] = backup[new_p2l[p]]
+            outcome[p] = FROM_DRAM if kind[p] == DRAM else FROM_DRAM_FALLBACK
+    return after, outcome
