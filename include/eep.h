@@ -301,6 +301,44 @@ int eep_plan_repair(int32_t R, int32_t S, int32_t S_prim, int32_t E,
                     int32_t* new_phys_to_logical, int32_t* source_kind, int32_t* source_slot,
                     int32_t summary[4]);
 
+/* Carry out a planned repair (Sec. 3.5: local reuse / batched GPU-to-GPU
+ * relocation / reload from the DRAM backup; Sec. 5.1: "moves weights to match
+ * that placement", the active mask being looked up when each transfer is
+ * issued), then publish the placement (as eep_update_placement does), all in
+ * stream order.
+ *   weights  device memory, [P][slot_bytes]: the expert weight store, slot-major
+ *            (rank r owns slots [r*S, (r+1)*S)); updated in place.
+ *   backup   [E][slot_bytes], readable by the GPU: device memory, or host memory
+ *            pinned with hipHostMalloc (the paper's DRAM backup; read over the
+ *            host link by the kernel).  May be NULL if the plan has no PEER and
+ *            no DRAM slot.
+ *   slot_bytes  > 0, multiple of 16; weights and backup 16-byte aligned.
+ *   new_phys_to_logical, source_kind, source_slot  host int32[P], as written by
+ *            eep_plan_repair for the placement this context holds now.
+ * One kernel does the whole batch.  For each PEER/DRAM slot p it reads the
+ * DEVICE copy of the active mask: destination rank inactive -> slot skipped;
+ * PEER and source rank active -> copy from source_slot[p]; otherwise (DRAM, or
+ * the planned source rank dropped out after planning) -> copy
+ * backup[new_phys_to_logical[p]].  What happened is recorded per slot
+ * (eep_repair_outcome) and read back with eep_read_repair_outcome.
+ * Checked on the host before anything is queued (EEP_ERR_INVALID_ARG):
+ * a LOCAL slot keeps the expert the context's current placement gives it; a PEER
+ * source is another slot that holds that expert now and is not itself rewritten
+ * by this batch; both pointers are what they are said to be (weights: a device
+ * allocation that contains all P slots; backup: GPU-accessible). */
+typedef enum {
+  EEP_REPAIR_UNTOUCHED = 0,
+  EEP_REPAIR_FROM_PEER = 1,
+  EEP_REPAIR_FROM_DRAM = 2,
+  EEP_REPAIR_FROM_DRAM_FALLBACK = 3, /* planned peer source was no longer active */
+  EEP_REPAIR_SKIPPED = 4             /* destination rank no longer active */
+} eep_repair_outcome;
+int eep_apply_repair(eep_ctx* ctx, void* weights, const void* backup, int64_t slot_bytes,
+                     const int32_t* new_phys_to_logical, const int32_t* source_kind,
+                     const int32_t* source_slot, void* stream);
+/* Outcome per slot of the last eep_apply_repair; synchronises the device. */
+int eep_read_repair_outcome(eep_ctx* ctx, int32_t* outcome_host);
+
 /* ---- hipGraph helper (Sec. 2.3, Fig. 4: capture once, replay, patch table
  * contents only) ------------------------------------------------------------
  * eep_graph_begin puts `stream` (not the default stream) into capture mode;

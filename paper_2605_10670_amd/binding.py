@@ -76,6 +76,8 @@ def load():
         "eep_host_uncovered_experts": [i32, i32, i32, vp, vp],
         "eep_host_tiling": [i32, i32, vp],
         "eep_plan_repair": [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp],
+        "eep_apply_repair": [vp, vp, vp, i64, vp, vp, vp, vp],
+        "eep_read_repair_outcome": [vp, vp],
         "eep_set_detection": [vp, i64],
         "eep_signal_experts_done": [vp, vp],
         "eep_debug_withhold_signal": [vp, vp, vp],
@@ -239,6 +241,23 @@ class Context:
             raise ValueError("phys_to_logical must have P entries")
         _check(load().eep_update_placement(self._h, p.ctypes.data, _stream(stream)),
                "eep_update_placement", self._h)
+
+    def apply_repair(self, weights, backup, slot_bytes, plan, stream=None):
+        """weights: device tensor [P, slot_bytes]; backup: device or pinned-host tensor
+        [E, slot_bytes] (or None); plan: the dict plan_repair returns."""
+        arrays = [np.ascontiguousarray(plan[key], np.int32) for key in ("p2l", "kind", "src_slot")]
+        if any(a.size != self.P for a in arrays):
+            raise ValueError("plan arrays must have P entries")
+        _check(load().eep_apply_repair(self._h, _ptr(weights), _ptr(backup), slot_bytes,
+                                       arrays[0].ctypes.data, arrays[1].ctypes.data,
+                                       arrays[2].ctypes.data, _stream(stream)),
+               "eep_apply_repair", self._h)
+
+    def read_repair_outcome(self):
+        out = np.zeros(self.P, np.int32)
+        _check(load().eep_read_repair_outcome(self._h, out.ctypes.data),
+               "eep_read_repair_outcome", self._h)
+        return out
 
     # -- per-step calls ------------------------------------------------------
     def dispatch_layout(self, topk_idx, T, stream=None):

@@ -123,7 +123,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) total += round_up(n[i] > 0 ? n[i] : 1);
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
   total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 3 * round_up(1) +
-           3 * round_up(c->R);
+           3 * round_up(c->R) + 4 * round_up(c->P);
   e = hipMalloc(&c->slab, (size_t)total * sizeof(int32_t));
   if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
   int32_t* cur = (int32_t*)c->slab;
@@ -140,7 +140,11 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   c->step_epoch = cur;  cur += round_up(1);
   c->signal = cur;      cur += round_up(c->R);
   c->withhold = cur;    cur += round_up(c->R);
-  c->report = cur;
+  c->report = cur;      cur += round_up(c->R);
+  c->mv_dst = cur;      cur += round_up(c->P);
+  c->mv_src = cur;      cur += round_up(c->P);
+  c->mv_expert = cur;   cur += round_up(c->P);
+  c->mv_outcome = cur;
   c->detect_timeout_ticks = 0;
   c->wall_clock_khz = 0;
 

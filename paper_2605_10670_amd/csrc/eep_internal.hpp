@@ -82,6 +82,9 @@ struct eep_ctx {
   // epoch of the last step whose expert outputs arrived), test knob that mutes
   // a rank, failure report written by the waiting kernel
   int32_t *step_epoch, *signal, *withhold, *report;
+  // repair batch: destination slot, source slot (-1 = backup), logical expert of
+  // each move, and what the relocation kernel did per slot
+  int32_t *mv_dst, *mv_src, *mv_expert, *mv_outcome;
   int64_t detect_timeout_ticks;  // 0 = detection off
   int wall_clock_khz;
 

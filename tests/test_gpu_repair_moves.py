@@ -1,0 +1,226 @@
+"""eep_apply_repair on the GPU against the oracle's weight movement (paper
+Sec. 3.5: local reuse / batched GPU-to-GPU relocation / DRAM reload; Sec. 5.1:
+the active mask is looked up when a transfer is issued).  Byte-exact."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import planner as ref
+from paper_2605_10670_amd import binding, synth
+from test_oracle_tables_map import parse_fig5
+from test_planner import _panel_placement
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _store(rng, p2l, E, slot_bytes):
+    """Backup of expert e: random bytes; the copy in slot q: the same bytes with
+    the slot id stamped over the first four, so the source of a copy is visible."""
+    backup = rng.integers(0, 256, size=(E, slot_bytes), dtype=np.uint8)
+    backup[:, :4] = 0
+    weights = np.empty((p2l.size, slot_bytes), np.uint8)
+    for q, e in enumerate(p2l):
+        weights[q] = backup[e] if e >= 0 else 0xEE
+        weights[q, :4] = np.frombuffer(np.int32(q + 1).tobytes(), np.uint8)
+    return weights, backup
+
+
+def _run(ctx, weights, backup, plan, slot_bytes, pinned):
+    w_dev = torch.from_numpy(weights).cuda()
+    if pinned:
+        b_dev = torch.empty(backup.shape, dtype=torch.uint8, pin_memory=True)
+        b_dev.copy_(torch.from_numpy(backup))
+    else:
+        b_dev = torch.from_numpy(backup).cuda()
+    ctx.apply_repair(w_dev, b_dev, slot_bytes, plan)
+    outcome = ctx.read_repair_outcome()
+    return w_dev.cpu().numpy(), outcome
+
+
+def _expect(weights, backup, plan, active_now, S):
+    after, outcome = ref.carry_out_repair([w.tobytes() for w in weights],
+                                          [b.tobytes() for b in backup], plan["p2l"],
+                                          plan["kind"], plan["src_slot"], active_now, S)
+    return np.frombuffer(b"".join(after), np.uint8).reshape(weights.shape), np.asarray(outcome)
+
+
+def _context(R, S, S_prim, E, strict=False):
+    return binding.Context(num_ranks=R, slots_per_rank=S, primary_slots=S_prim, num_logical=E,
+                           max_tokens=R * 4, topk=min(2, E), hidden=64, strict_coverage=strict)
+
+
+@pytest.mark.parametrize("pinned", [False, True])
+def test_fig5_repair_moves(pinned):
+    meta, panels = parse_fig5()
+    S, S_prim, E, R = meta["slots_per_rank"], meta["primary_slots"], meta["experts"], 4
+    before = _panel_placement(panels[0], R, S)
+    active = np.asarray(panels[1]["active"], np.int32)
+    slot_bytes = 3 * 65536 + 48                                   # several chunks and a ragged tail
+    weights, backup = _store(np.random.default_rng(5), before, E, slot_bytes)
+    ctx = _context(R, S, S_prim, E, strict=True)
+    try:
+        ctx.update_placement(before)
+        plan = binding.plan_repair(before, active, R, S, S_prim, E)
+        got_w, got_o = _run(ctx, weights, backup, plan, slot_bytes, pinned)
+        want_w, want_o = _expect(weights, backup, plan, np.ones(R, np.int32), S)
+        assert np.array_equal(got_o, want_o)
+        assert np.array_equal(got_w, want_w)
+        assert got_o[0 * S + 2] == ref.FROM_DRAM and got_o[1 * S + 2] == ref.FROM_PEER
+        # the placement went live with the weights: membership can shrink under strict coverage
+        assert ctx.read("phys_to_logical", R * S).tolist() == plan["p2l"].tolist()
+        ctx.set_membership(active)
+    finally:
+        ctx.destroy()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_repairs_match_oracle(seed):
+    rng = np.random.default_rng(300 + seed)
+    for trial in range(6):
+        R, S = int(rng.integers(2, 10)), int(rng.integers(1, 5))
+        S_prim = int(rng.integers(0, S + 1))
+        E = int(rng.integers(1, R * S + 3))
+        slot_bytes = int(rng.choice([16, 48, 4096, 65536, 65536 + 16, 200000 // 16 * 16, 1 << 20]))
+        cur = rng.integers(-1, E, size=R * S).astype(np.int32)
+        active = (rng.random(R) < 0.7).astype(np.int32)
+        active[int(rng.integers(R))] = 1
+        plan = binding.plan_repair(cur, active, R, S, S_prim, E)
+        weights, backup = _store(rng, cur, E, slot_bytes)
+        later = active.copy()
+        if trial % 2 and active.sum() > 1:                        # a rank drops out after planning
+            later[rng.choice(np.nonzero(active)[0])] = 0
+        ctx = _context(R, S, S_prim, E)
+        try:
+            ctx.update_placement(cur)
+            ctx.set_membership(later)
+            got_w, got_o = _run(ctx, weights, backup, plan, slot_bytes, pinned=bool(trial % 3 == 0))
+            want_w, want_o = _expect(weights, backup, plan, later, S)
+            assert np.array_equal(got_o, want_o), (seed, trial)
+            assert np.array_equal(got_w, want_w), (seed, trial)
+            assert ctx.read("phys_to_logical", R * S).tolist() == plan["p2l"].tolist()
+        finally:
+            ctx.destroy()
+
+
+def test_decode_shape_repair_then_step(oracle):
+    """32 ranks x (8+1) slots, rank 13 fails: plan, move weights, publish, then run a
+    step under the repaired tables and compare its layout with the oracle."""
+    wl = synth.decode(T=512, H=256, seed_offset=31)
+    R, S, S_prim, E = wl.R, wl.S, wl.S_prim, wl.E
+    dead = synth.active_mask(R, (13,))
+    slot_bytes = 1 << 20
+    weights, backup = _store(np.random.default_rng(9), wl.p2l, E, slot_bytes)
+    ctx = gu.make_context(wl)
+    try:
+        ctx.update_placement(wl.p2l)
+        plan = binding.plan_repair(wl.p2l, dead, R, S, S_prim, E)
+        assert plan["unplaced"] == 0 and plan["dram"] + plan["peer"] > 0
+        got_w, got_o = _run(ctx, weights, backup, plan, slot_bytes, pinned=True)
+        want_w, want_o = _expect(weights, backup, plan, np.ones(R, np.int32), S)
+        assert np.array_equal(got_o, want_o) and np.array_equal(got_w, want_w)
+        # every live slot now holds the weights of the expert the placement names
+        for p in np.nonzero(np.repeat(dead, S))[0]:
+            if plan["p2l"][p] >= 0:
+                assert np.array_equal(got_w[p, 4:], backup[plan["p2l"][p], 4:])
+        ctx.set_membership(dead)
+        dev = gu.DeviceStep(ctx, wl)
+        dev.step()
+        dev.sync()
+        lay = oracle.step_layout(wl.topk_idx, plan["p2l"], dead, E, R, S, S_prim, oracle.SPREAD)
+        gu.assert_layout_equal(ctx.read_layout(wl.T), lay, wl.T, wl.k)
+        assert lay["n_uncovered"] == 0
+    finally:
+        ctx.destroy()
+
+
+def test_refused_before_anything_is_queued():
+    R, S, S_prim, E = 4, 3, 2, 8
+    meta, panels = parse_fig5()
+    before = _panel_placement(panels[0], R, S)
+    active = np.asarray(panels[1]["active"], np.int32)
+    slot_bytes = 4096
+    weights, backup = _store(np.random.default_rng(1), before, E, slot_bytes)
+    w_dev, b_dev = torch.from_numpy(weights).cuda(), torch.from_numpy(backup).cuda()
+    ctx = _context(R, S, S_prim, E)
+    try:
+        ctx.update_placement(before)
+        good = binding.plan_repair(before, active, R, S, S_prim, E)
+
+        def refused(code, w=w_dev, b=b_dev, nbytes=slot_bytes, **changes):
+            plan = {key: np.array(val, copy=True) if isinstance(val, np.ndarray) else val
+                    for key, val in good.items()}
+            for key, (slot, val) in changes.items():
+                plan[key][slot] = val
+            with pytest.raises(binding.EepError) as ei:
+                ctx.apply_repair(w, b, nbytes, plan)
+            assert ei.value.code == code
+
+        refused(binding.ERR_INVALID_ARG, p2l=(0, 5))              # "local" slot that holds E0, not E5
+        refused(binding.ERR_INVALID_ARG, src_slot=(1 * S + 2, 0)) # peer source holds another expert
+        refused(binding.ERR_INVALID_ARG, src_slot=(1 * S + 2, 99))
+        refused(binding.ERR_INVALID_ARG, kind=(3 * S + 2, binding.SRC_DRAM))  # source rewritten too
+        refused(binding.ERR_INVALID_ARG, kind=(0, 7))
+        refused(binding.ERR_INVALID_ARG, b=None)                  # moves planned, no backup
+        refused(binding.ERR_ALIGN, nbytes=slot_bytes + 8)
+        refused(binding.ERR_INVALID_ARG, nbytes=0)
+        # an allocation too small for P slots (a fresh large block: torch's caching allocator
+        # adds no slack to those, and the check is against the enclosing hipMalloc)
+        torch.cuda.empty_cache()
+        big = 16 << 20
+        refused(binding.ERR_INVALID_ARG, nbytes=big,
+                w=torch.empty((R * S - 2) * big, dtype=torch.uint8, device="cuda"),
+                b=torch.empty(E * big, dtype=torch.uint8, device="cuda"))
+        host_plain = np.zeros((E, slot_bytes), np.uint8)          # pageable host memory
+        refused(binding.ERR_INVALID_ARG, b=host_plain.ctypes.data)
+        pinned = torch.empty((R * S, slot_bytes), dtype=torch.uint8, pin_memory=True)
+        refused(binding.ERR_INVALID_ARG, w=pinned)                # the store itself must be on the GPU
+        # nothing was moved or published by the refused calls
+        assert np.array_equal(w_dev.cpu().numpy(), weights)
+        assert ctx.read("phys_to_logical", R * S).tolist() == before.tolist()
+        ctx.apply_repair(w_dev, b_dev, slot_bytes, good)          # and the good plan still goes through
+        assert ctx.read_repair_outcome().tolist().count(ref.UNTOUCHED) == R * S - 2
+    finally:
+        ctx.destroy()
+
+
+def test_source_rank_dropped_by_the_gpu_after_planning():
+    """The planned peer source lives on a rank that the waiting kernel drops (Sec. 4.1)
+    before the transfers are issued; the host's copy of the mask is stale.  The
+    relocation kernel reads the device mask and takes the DRAM backup (Sec. 5.1)."""
+    base = synth.churn_inputs(1, T=512, H=512)[0]
+    R, S_prim, E = base.R, base.S_prim, base.E
+    S = S_prim + 2                                                 # a second, empty redundant slot
+    p2l = np.full((R, S), -1, np.int32)
+    p2l[:, :S_prim + 1] = base.p2l.reshape(R, -1)
+    wl = dataclasses.replace(base, S_red=2, p2l=p2l.ravel().copy())
+    failed = 3
+    plan = binding.plan_repair(wl.p2l, synth.active_mask(R, (failed,)), R, S, S_prim, E)
+    peers = np.nonzero(plan["kind"] == binding.SRC_PEER)[0]
+    assert peers.size > 0
+    silent = int(plan["src_slot"][peers[0]] // S)                  # rank of a planned source
+    assert silent != failed
+    slot_bytes = 65536 + 32
+    weights, backup = _store(np.random.default_rng(17), wl.p2l, E, slot_bytes)
+    ctx = gu.make_context(wl, strict=False)
+    try:
+        gu.apply_tables(ctx, wl.p2l, synth.active_mask(R, (failed,)))
+        ctx.set_detection(200_000)
+        mute = np.zeros(R, np.int32)
+        mute[silent] = 1
+        ctx.debug_withhold_signal(mute)
+        dev = gu.DeviceStep(ctx, wl)
+        dev.step()                                                 # the wait times out: rank dropped
+        dev.sync()
+        now = synth.active_mask(R, (failed, silent))
+        assert ctx.read("active", R).tolist() == now.tolist()
+        got_w, got_o = _run(ctx, weights, backup, plan, slot_bytes, pinned=False)
+        want_w, want_o = _expect(weights, backup, plan, now, S)
+        assert np.array_equal(got_o, want_o) and np.array_equal(got_w, want_w)
+        assert got_o[peers[0]] in (ref.FROM_DRAM_FALLBACK, ref.SKIPPED)
+        assert (got_o == ref.FROM_DRAM_FALLBACK).sum() + (got_o == ref.SKIPPED).sum() > 0
+    finally:
+        ctx.destroy()
