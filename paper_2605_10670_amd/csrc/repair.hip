@@ -38,21 +38,22 @@ __global__ __launch_bounds__(kMoveThreads) void k_relocate(
   const u32x4* from = from_peer ? weights + (int64_t)src * slot_vecs : backup + (int64_t)e * slot_vecs;
   u32x4* to = weights + (int64_t)dst * slot_vecs;
   const int64_t first = (int64_t)chunk * kChunkVecs + threadIdx.x;
+  if ((int64_t)(chunk + 1) * kChunkVecs <= slot_vecs) {
+    // full chunk: no per-vector guards, so all loads of a pass are in flight together
 #pragma unroll
-  for (int pass = 0; pass < kMovePasses; ++pass) {
-    const int64_t base = first + (int64_t)pass * (kMoveThreads * kMoveVecs);
-    u32x4 buf[kMoveVecs];
+    for (int pass = 0; pass < kMovePasses; ++pass) {
+      const int64_t base = first + (int64_t)pass * (kMoveThreads * kMoveVecs);
+      u32x4 buf[kMoveVecs];
 #pragma unroll
-    for (int u = 0; u < kMoveVecs; ++u) {
-      const int64_t v = base + (int64_t)u * kMoveThreads;
-      if (v < slot_vecs) buf[u] = __builtin_nontemporal_load(from + v);
+      for (int u = 0; u < kMoveVecs; ++u)
+        buf[u] = __builtin_nontemporal_load(from + base + (int64_t)u * kMoveThreads);
+#pragma unroll
+      for (int u = 0; u < kMoveVecs; ++u) to[base + (int64_t)u * kMoveThreads] = buf[u];
     }
-#pragma unroll
-    for (int u = 0; u < kMoveVecs; ++u) {
-      const int64_t v = base + (int64_t)u * kMoveThreads;
-      if (v < slot_vecs) to[v] = buf[u];
-    }
+    return;
   }
+  // ragged last chunk of a slot
+  for (int64_t v = first; v < slot_vecs; v += kMoveThreads) to[v] = __builtin_nontemporal_load(from + v);
 }
 
 int fail_hip(eep_ctx* c, hipError_t e) {
