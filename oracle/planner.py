@@ -67,30 +67,59 @@ def plan_repair(cur, active, R, S, S_prim, E, load=None):
                 dram=kind.count(DRAM), unplaced=unplaced)
 
 
+def plan_transition(cur, target, active, writable, R, S, S_prim):
+    """Sources for moving from placement `cur` to a given `target` placement -- the
+    step "resume preferred placement" of the reintegration sequence (Sec. 3.6,
+    Fig. 5 right panel), classified with Sec. 3.5's hierarchy.  active[r]: rank r
+    holds usable copies (a possible source); writable[r]: rank r's slots may be
+    filled (active ranks plus a relaunched rank that is loading its experts before
+    it reports join-ready).  A source is a slot on an active rank that holds the
+    expert now and receives no new weights in this batch; among several, primary
+    slots first, then the lowest slot id.  Slots of non-writable ranks keep `cur`.
+    """
+    P = R * S
+    cur, target = [int(v) for v in cur], [int(v) for v in target]
+    new = [target[p] if writable[p // S] else cur[p] for p in range(P)]
+    rewritten = [bool(writable[p // S]) and new[p] >= 0 and new[p] != cur[p] for p in range(P)]
+    kind, src = [NONE] * P, [-1] * P
+    for p in range(P):
+        if not writable[p // S] or new[p] < 0:
+            continue
+        if not rewritten[p]:
+            kind[p] = LOCAL
+            continue
+        holders = [q for q in range(P) if active[q // S] and cur[q] == new[p] and not rewritten[q]]
+        if holders:
+            kind[p] = PEER
+            src[p] = min(holders, key=lambda q: ((q % S) >= S_prim, q))
+        else:
+            kind[p] = DRAM
+    return dict(p2l=new, kind=kind, src_slot=src, local=kind.count(LOCAL), peer=kind.count(PEER),
+                dram=kind.count(DRAM), unplaced=0)
+
+
 # outcome per slot of carry_out_repair
-UNTOUCHED, FROM_PEER, FROM_DRAM, FROM_DRAM_FALLBACK, SKIPPED = 0, 1, 2, 3, 4
+UNTOUCHED, FROM_PEER, FROM_DRAM, FROM_DRAM_FALLBACK = 0, 1, 2, 3
 
 
 def carry_out_repair(weights, backup, new_p2l, kind, src_slot, active_now, S):
     """Weight movement that satisfies a planned placement (Sec. 3.5's source
     hierarchy; Sec. 5.1: the active mask is looked up when a transfer is issued,
     and an expert whose planned source rank has gone inactive since the plan was
-    made is filled from the DRAM backup instead).
+    made is filled from the DRAM backup instead).  Only the SOURCE rank is looked
+    up: a destination may be a rank that is not active yet (Sec. 3.6: a relaunched
+    rank loads its experts before it is join-ready).
 
     weights: list of P byte strings (what each slot holds now); backup: list of E
-    byte strings.  Slots planned as already-local or empty are not touched; a
-    destination on a rank that is no longer active is skipped.  Every transfer
-    reads the state before the batch (a source is never also a destination).
-    Returns (new weights, outcome per slot).
+    byte strings.  Slots planned as already-local or empty are not touched.  Every
+    transfer reads the state before the batch (a source is never also a
+    destination).  Returns (new weights, outcome per slot).
     """
     P = len(weights)
     after = list(weights)
     outcome = [UNTOUCHED] * P
     for p in range(P):
         if kind[p] != PEER and kind[p] != DRAM:
-            continue
-        if not active_now[p // S]:
-            outcome[p] = SKIPPED
             continue
         if kind[p] == PEER and active_now[src_slot[p] // S]:
             after[p] = weights[src_slot[p]]

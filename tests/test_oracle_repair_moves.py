@@ -69,9 +69,6 @@ def test_every_live_slot_ends_up_holding_what_the_placement_names(seed):
             if kind in (ref.NONE, ref.LOCAL):
                 assert after[p] == weights[p] and outcome[p] == ref.UNTOUCHED
                 continue
-            if not later[p // S]:
-                assert after[p] == weights[p] and outcome[p] == ref.SKIPPED
-                continue
             assert after[p][1:] == backup[e][1:]                  # the right expert's weights
             if kind == ref.DRAM:
                 assert after[p][0] == 0 and outcome[p] == ref.FROM_DRAM
@@ -84,3 +81,69 @@ def test_every_live_slot_ends_up_holding_what_the_placement_names(seed):
         # a planned source is never overwritten by the same batch
         dests = {p for p in range(R * S) if plan["kind"][p] in (ref.PEER, ref.DRAM)}
         assert not dests & {plan["src_slot"][p] for p in dests if plan["kind"][p] == ref.PEER}
+
+
+def _rejoin_plan(impl_transition):
+    meta, panels = parse_fig5()
+    S, S_prim, E, R = meta["slots_per_rank"], meta["primary_slots"], meta["experts"], 4
+    normal = _panel_placement(panels[0], R, S)
+    shrunk_mask = np.asarray(panels[1]["active"], np.int32)
+    shrunk = _panel_placement(panels[1], R, S, stale=normal)
+    shrunk[2 * S:3 * S] = -1                                      # the relaunched rank holds nothing yet
+    target = _panel_placement(panels[2], R, S)
+    assert np.array_equal(target, normal)                         # Fig. 5: the preferred placement returns
+    plan = impl_transition(shrunk, target, shrunk_mask, np.ones(R, np.int32), R, S, S_prim)
+    return S, E, shrunk, target, shrunk_mask, plan
+
+
+def test_fig5_rejoin_restores_the_preferred_placement():
+    S, E, shrunk, target, mask, plan = _rejoin_plan(ref.plan_transition)
+    assert plan["p2l"] == target.tolist()
+    kind, src = plan["kind"], plan["src_slot"]
+    # R2 gets E2 and E6 back from the copies the repair made on R1 and R0
+    assert kind[2 * S] == ref.PEER and src[2 * S] == 1 * S + 2
+    assert kind[2 * S + 1] == ref.PEER and src[2 * S + 1] == 0 * S + 2
+    # the repair's extra copies are given up (slots empty again), everything else stays
+    assert kind[0 * S + 2] == ref.NONE and kind[1 * S + 2] == ref.NONE
+    assert plan["local"] == 7 and plan["peer"] == 2 and plan["dram"] == 0
+    weights, backup = tagged_store(shrunk, E)
+    after, outcome = ref.carry_out_repair(weights, backup, plan["p2l"], kind, src, mask, S)
+    for p, e in enumerate(target):                                # loaded while R2 is still inactive
+        if e >= 0:
+            assert after[p][1:] == backup[e][1:]
+    assert after[2 * S][0] == (1 * S + 2) + 1 and after[2 * S + 1][0] == (0 * S + 2) + 1
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_transition_plans_reach_any_target(seed):
+    rng = np.random.default_rng(500 + seed)
+    for trial in range(60):
+        R, S = int(rng.integers(2, 9)), int(rng.integers(1, 5))
+        S_prim = int(rng.integers(0, S + 1))
+        E = int(rng.integers(1, min(R * S + 3, 250)))
+        cur = rng.integers(-1, E, size=R * S).astype(np.int32)
+        target = rng.integers(-1, E, size=R * S).astype(np.int32)
+        active = (rng.random(R) < 0.7).astype(np.int32)
+        writable = np.maximum(active, (rng.random(R) < 0.3).astype(np.int32))
+        plan = ref.plan_transition(cur, target, active, writable, R, S, S_prim)
+        weights, backup = tagged_store(cur, E)
+        after, outcome = ref.carry_out_repair(weights, backup, plan["p2l"], plan["kind"],
+                                              plan["src_slot"], active, S)
+        for p in range(R * S):
+            if not writable[p // S]:
+                assert plan["p2l"][p] == cur[p] and after[p] == weights[p]
+                continue
+            e = plan["p2l"][p]
+            assert e == target[p]
+            if e < 0:
+                assert after[p] == weights[p]
+            elif e == cur[p]:
+                assert after[p] == weights[p] and plan["kind"][p] == ref.LOCAL
+            else:
+                assert after[p][1:] == backup[e][1:]
+                live_copy = any(active[q // S] and cur[q] == e and
+                                not (writable[q // S] and target[q] >= 0 and target[q] != cur[q])
+                                for q in range(R * S))
+                assert (plan["kind"][p] == ref.PEER) == live_copy  # DRAM only when no copy survives
+                if live_copy:
+                    assert after[p][0] == plan["src_slot"][p] + 1
