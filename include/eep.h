@@ -301,6 +301,26 @@ int eep_plan_repair(int32_t R, int32_t S, int32_t S_prim, int32_t E,
                     int32_t* new_phys_to_logical, int32_t* source_kind, int32_t* source_slot,
                     int32_t summary[4]);
 
+/* Sources for moving from the current placement to a GIVEN target placement:
+ * the step "resume preferred placement and full capacity" of the reintegration
+ * sequence (Sec. 3.6; Fig. 5, right panel), classified with the same hierarchy
+ * as eep_plan_repair.  Host only.
+ *   active[R]    ranks whose copies can serve as sources;
+ *   writable[R]  ranks whose slots may be filled: the active ranks plus, during
+ *                reintegration, the relaunched rank, which loads its experts
+ *                before it reports join-ready (mark the slots it lost as -1 in
+ *                cur_phys_to_logical).
+ * new_phys_to_logical[p] = target[p] on writable ranks, cur[p] elsewhere.  A slot
+ * whose expert does not change is LOCAL; otherwise PEER from a slot on an active
+ * rank that holds the expert now and gets no new weights in this batch (primary
+ * slots first, then lowest slot id), else DRAM.  summary = {local, peer, dram, 0}.
+ * Returns EEP_OK or EEP_ERR_INVALID_ARG. */
+int eep_plan_transition(int32_t R, int32_t S, int32_t S_prim, int32_t E,
+                        const int32_t* cur_phys_to_logical, const int32_t* target_phys_to_logical,
+                        const int32_t* active, const int32_t* writable,
+                        int32_t* new_phys_to_logical, int32_t* source_kind, int32_t* source_slot,
+                        int32_t summary[4]);
+
 /* Carry out a planned repair (Sec. 3.5: local reuse / batched GPU-to-GPU
  * relocation / reload from the DRAM backup; Sec. 5.1: "moves weights to match
  * that placement", the active mask being looked up when each transfer is
@@ -315,11 +335,13 @@ int eep_plan_repair(int32_t R, int32_t S, int32_t S_prim, int32_t E,
  *   slot_bytes  > 0, multiple of 16; weights and backup 16-byte aligned.
  *   new_phys_to_logical, source_kind, source_slot  host int32[P], as written by
  *            eep_plan_repair for the placement this context holds now.
- * One kernel does the whole batch.  For each PEER/DRAM slot p it reads the
- * DEVICE copy of the active mask: destination rank inactive -> slot skipped;
- * PEER and source rank active -> copy from source_slot[p]; otherwise (DRAM, or
- * the planned source rank dropped out after planning) -> copy
- * backup[new_phys_to_logical[p]].  What happened is recorded per slot
+ *            (eep_plan_transition's output is accepted as well).
+ * One kernel does the whole batch.  For each PEER slot p it reads the DEVICE
+ * copy of the active mask: source rank active -> copy from source_slot[p];
+ * source rank dropped out after planning -> copy backup[new_phys_to_logical[p]]
+ * instead.  DRAM slots copy from the backup.  Only the source is looked up: the
+ * destination may be a rank that is not active yet (Sec. 3.6: a relaunched rank
+ * loads its experts before it joins).  What happened is recorded per slot
  * (eep_repair_outcome) and read back with eep_read_repair_outcome.
  * Checked on the host before anything is queued (EEP_ERR_INVALID_ARG):
  * a LOCAL slot keeps the expert the context's current placement gives it; a PEER
@@ -330,8 +352,7 @@ typedef enum {
   EEP_REPAIR_UNTOUCHED = 0,
   EEP_REPAIR_FROM_PEER = 1,
   EEP_REPAIR_FROM_DRAM = 2,
-  EEP_REPAIR_FROM_DRAM_FALLBACK = 3, /* planned peer source was no longer active */
-  EEP_REPAIR_SKIPPED = 4             /* destination rank no longer active */
+  EEP_REPAIR_FROM_DRAM_FALLBACK = 3 /* planned peer source was no longer active */
 } eep_repair_outcome;
 int eep_apply_repair(eep_ctx* ctx, void* weights, const void* backup, int64_t slot_bytes,
                      const int32_t* new_phys_to_logical, const int32_t* source_kind,

@@ -76,6 +76,7 @@ def load():
         "eep_host_uncovered_experts": [i32, i32, i32, vp, vp],
         "eep_host_tiling": [i32, i32, vp],
         "eep_plan_repair": [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp],
+        "eep_plan_transition": [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp],
         "eep_apply_repair": [vp, vp, vp, i64, vp, vp, vp, vp],
         "eep_read_repair_outcome": [vp, vp],
         "eep_set_detection": [vp, i64],
@@ -183,6 +184,22 @@ def plan_repair(cur_p2l, active, R, S, S_prim, E, load=None):
         _check(rc, "eep_plan_repair")
     return dict(p2l=new, kind=kind, src_slot=src, local=int(summary[0]), peer=int(summary[1]),
                 dram=int(summary[2]), unplaced=int(summary[3]))
+
+
+def plan_transition(cur_p2l, target_p2l, active, writable, R, S, S_prim, E):
+    """Sources for moving to a given target placement (host only); same dict as plan_repair."""
+    cur, tgt = (np.ascontiguousarray(a, np.int32) for a in (cur_p2l, target_p2l))
+    act, wr = (np.ascontiguousarray(a, np.int32) for a in (active, writable))
+    if cur.size != R * S or tgt.size != R * S or act.size != R or wr.size != R:
+        raise ValueError("placements must have R*S entries and masks R")
+    new, kind, src = (np.empty(R * S, np.int32) for _ in range(3))
+    summary = np.zeros(4, np.int32)
+    _check(_library().eep_plan_transition(R, S, S_prim, E, cur.ctypes.data, tgt.ctypes.data,
+                                          act.ctypes.data, wr.ctypes.data, new.ctypes.data,
+                                          kind.ctypes.data, src.ctypes.data, summary.ctypes.data),
+           "eep_plan_transition")
+    return dict(p2l=new, kind=kind, src_slot=src, local=int(summary[0]), peer=int(summary[1]),
+                dram=int(summary[2]), unplaced=0)
 
 
 class Graph:

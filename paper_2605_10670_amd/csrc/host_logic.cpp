@@ -190,9 +190,52 @@ int host_plan_repair(int R, int S, int S_prim, int E, const int32_t* cur, const 
   return unplaced;
 }
 
+void host_plan_transition(int R, int S, int S_prim, const int32_t* cur, const int32_t* target,
+                          const int32_t* active, const int32_t* writable, int32_t* new_p2l,
+                          int32_t* kind, int32_t* src_slot, int32_t summary[4]) {
+  const int P = R * S;
+  std::vector<char> gets_weights(P, 0);
+  for (int p = 0; p < P; ++p) {
+    new_p2l[p] = writable[p / S] ? target[p] : cur[p];
+    gets_weights[p] = writable[p / S] && new_p2l[p] >= 0 && new_p2l[p] != cur[p];
+    kind[p] = EEP_SRC_NONE;
+    src_slot[p] = -1;
+  }
+  int n_local = 0, n_peer = 0, n_dram = 0;
+  for (int p = 0; p < P; ++p) {
+    if (!writable[p / S] || new_p2l[p] < 0) continue;
+    if (!gets_weights[p]) { kind[p] = EEP_SRC_LOCAL; ++n_local; continue; }
+    // canonical order: primary slots of all ranks first, then redundant ones
+    int found = -1;
+    for (int pass = 0; pass < 2 && found < 0; ++pass)
+      for (int q = 0; q < P && found < 0; ++q)
+        if (((q % S) >= S_prim) == (pass == 1) && active[q / S] && cur[q] == new_p2l[p] &&
+            !gets_weights[q])
+          found = q;
+    if (found >= 0) { kind[p] = EEP_SRC_PEER; src_slot[p] = found; ++n_peer; }
+    else { kind[p] = EEP_SRC_DRAM; ++n_dram; }
+  }
+  summary[0] = n_local; summary[1] = n_peer; summary[2] = n_dram; summary[3] = 0;
+}
+
 }  // namespace eep
 
 extern "C" {
+
+int eep_plan_transition(int32_t R, int32_t S, int32_t S_prim, int32_t E, const int32_t* cur_p2l,
+                        const int32_t* target_p2l, const int32_t* active, const int32_t* writable,
+                        int32_t* new_p2l, int32_t* source_kind, int32_t* source_slot,
+                        int32_t summary[4]) {
+  if (R < 1 || S < 1 || S_prim < 0 || S_prim > S || E < 1 || !cur_p2l || !target_p2l || !active ||
+      !writable || !new_p2l || !source_kind || !source_slot || !summary)
+    return EEP_ERR_INVALID_ARG;
+  for (int p = 0; p < R * S; ++p)
+    if (cur_p2l[p] < -1 || cur_p2l[p] >= E || target_p2l[p] < -1 || target_p2l[p] >= E)
+      return EEP_ERR_INVALID_ARG;
+  eep::host_plan_transition(R, S, S_prim, cur_p2l, target_p2l, active, writable, new_p2l,
+                            source_kind, source_slot, summary);
+  return EEP_OK;
+}
 
 int eep_plan_repair(int32_t R, int32_t S, int32_t S_prim, int32_t E, const int32_t* cur_p2l,
                     const int32_t* active, const float* load, int32_t* new_p2l,

@@ -26,15 +26,13 @@ __global__ __launch_bounds__(kMoveThreads) void k_relocate(
   const int m = blockIdx.x / chunks_per_move;
   const int chunk = blockIdx.x - m * chunks_per_move;
   const int dst = mv_dst[m], src = mv_src[m], e = mv_expert[m];
-  // the mask as it stands now, not as it stood when the plan was made
-  const bool dst_live = active[dst / S] != 0;
+  // the mask as it stands now, not as it stood when the plan was made; only the
+  // source is looked up (a destination may belong to a rank that has not joined yet)
   const bool from_peer = src >= 0 && active[src / S] != 0;
   if (chunk == 0 && threadIdx.x == 0)
-    outcome[dst] = !dst_live   ? EEP_REPAIR_SKIPPED
-                   : from_peer ? EEP_REPAIR_FROM_PEER
-                   : src >= 0  ? EEP_REPAIR_FROM_DRAM_FALLBACK
-                               : EEP_REPAIR_FROM_DRAM;
-  if (!dst_live) return;
+    outcome[dst] = from_peer ? EEP_REPAIR_FROM_PEER
+                   : src >= 0 ? EEP_REPAIR_FROM_DRAM_FALLBACK
+                              : EEP_REPAIR_FROM_DRAM;
   const u32x4* from = from_peer ? weights + (int64_t)src * slot_vecs : backup + (int64_t)e * slot_vecs;
   u32x4* to = weights + (int64_t)dst * slot_vecs;
   const int64_t first = (int64_t)chunk * kChunkVecs + threadIdx.x;

@@ -138,3 +138,34 @@ def test_bad_arguments():
         binding.plan_repair(np.array([0, 9], np.int32), [1, 1], 2, 1, 1, 2)
     with pytest.raises(binding.EepError):
         binding.plan_repair(np.array([0, 1], np.int32), [1, 1], 2, 1, 1, 2, load=[-1.0, 1.0])
+
+
+def test_transition_library_matches_plain_statement():
+    rng = np.random.default_rng(77)
+    for trial in range(300):
+        R, S = int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        S_prim = int(rng.integers(0, S + 1))
+        E = int(rng.integers(1, R * S + 3))
+        cur = rng.integers(-1, E, size=R * S).astype(np.int32)
+        target = rng.integers(-1, E, size=R * S).astype(np.int32)
+        if trial % 3 == 0:                                         # mostly-unchanged targets too
+            keep = rng.random(R * S) < 0.8
+            target[keep] = cur[keep]
+        active = (rng.random(R) < 0.7).astype(np.int32)
+        writable = np.maximum(active, (rng.random(R) < 0.3).astype(np.int32))
+        got = binding.plan_transition(cur, target, active, writable, R, S, S_prim, E)
+        want = ref.plan_transition(cur, target, active, writable, R, S, S_prim)
+        for key in ("p2l", "kind", "src_slot"):
+            assert np.asarray(got[key]).tolist() == list(want[key]), (trial, key)
+        assert (got["local"], got["peer"], got["dram"]) == (want["local"], want["peer"], want["dram"])
+
+
+def test_transition_argument_errors():
+    ok = np.zeros(4, np.int32)
+    one = np.ones(2, np.int32)
+    with pytest.raises(binding.EepError):
+        binding.plan_transition(ok, np.array([0, 0, 0, 9], np.int32), one, one, 2, 2, 1, 4)
+    with pytest.raises(binding.EepError):
+        binding.plan_transition(ok - 2, ok, one, one, 2, 2, 1, 4)
+    with pytest.raises(ValueError):
+        binding.plan_transition(ok, ok, one, np.ones(3, np.int32), 2, 2, 1, 4)
