@@ -100,3 +100,76 @@ def test_churn_1000_replays_one_instantiation(oracle):
         graph.destroy()
     finally:
         ctx.destroy()
+
+
+def test_decode_full_size_as_the_benchmark_launches_it(oracle):
+    """The launch configuration the benchmark times: DeepSeek-V3 decode shape at full
+    size, identity expert (y aliases the receive buffer), EIGHT steps captured in one
+    hipGraph on a side stream, replayed with table patches and eager work in between.
+    Every output row of every step of every replay is compared with the oracle."""
+    wl = synth.decode()
+    T, k, H, R = wl.T, wl.k, wl.H, wl.R
+    failed = (13,)
+    dead, live = synth.active_mask(R, failed), synth.active_mask(R)
+    repaired = synth.repaired_placement(wl.p2l, failed, R, wl.S_prim, wl.S_red)
+
+    def expected(p2l, active):
+        lay = oracle.step_layout(wl.topk_idx, p2l, active, wl.E, R, wl.S, wl.S_prim, oracle.SPREAD)
+        recv = oracle.pack(wl.x, lay["row_of"])
+        chain = oracle.f32_to_bf16(oracle.combine_chain32(recv, oracle.BF16, wl.topk_w, lay["row_of"]))
+        gu.check_combine(chain, "bf16", oracle.combine(recv, oracle.BF16, wl.topk_w, lay["row_of"]))
+        return lay, recv, chain
+
+    want_live, want_dead = expected(wl.p2l, live), expected(repaired, dead)
+    assert want_dead[0]["rank_count"][13] == 0 and want_dead[0]["N"] == T * k
+
+    ctx = gu.make_context(wl)
+    stream = torch.cuda.Stream()
+    steps_per_graph = 8
+    try:
+        gu.apply_tables(ctx, wl.p2l, live, stream)
+        idx, w, x = gu.to_dev(wl.topk_idx), gu.to_dev(wl.topk_w), gu.to_dev(wl.x)
+        recv = torch.zeros((T * k, H), dtype=torch.int16, device="cuda")
+        outs = [torch.zeros((T, H), dtype=torch.int16, device="cuda") for _ in range(steps_per_graph)]
+        torch.cuda.synchronize()
+
+        def step(out):
+            ctx.dispatch_layout(idx, T, stream)
+            ctx.dispatch(x, recv, T, stream=stream)
+            ctx.combine(recv, w, out, T, stream=stream)
+
+        step(outs[0])
+        stream.synchronize()
+        ctx.graph_begin(stream)
+        for out in outs:
+            step(out)
+        graph = ctx.graph_end(stream)
+
+        def replay_and_check(want, version):
+            for out in outs:
+                out.zero_()
+            torch.cuda.synchronize()
+            graph.launch(stream)
+            stream.synchronize()
+            lay, rows, chain = want
+            got = ctx.read_layout(T, stream)
+            gu.assert_layout_equal(got, lay, T, k)
+            assert got["version"] == version
+            assert np.array_equal(gu.to_host(recv, np.uint16)[:lay["N"]], rows[:lay["N"]])
+            for i, out in enumerate(outs):
+                assert np.array_equal(gu.to_host(out, np.uint16), chain), f"step {i} of the graph"
+
+        replay_and_check(want_live, 2)
+        ctx.update_placement(repaired, stream)          # rank 13 fails: two table patches
+        ctx.set_membership(dead, stream)
+        replay_and_check(want_dead, 4)
+        step(outs[0])                                   # eager work between replays
+        stream.synchronize()
+        replay_and_check(want_dead, 4)
+        ctx.set_membership(live, stream)                # and rejoins
+        ctx.update_placement(wl.p2l, stream)
+        replay_and_check(want_live, 6)
+        assert graph.counters() == dict(instantiations=1, exec_updates=0, launches=4)
+        graph.destroy()
+    finally:
+        ctx.destroy()
