@@ -291,6 +291,69 @@ def test_prefill_fp8_full_size_sampled(oracle):
         ctx.destroy()
 
 
+def test_buffers_beyond_4_gib_sampled(oracle):
+    """32x the decode batch (T=131072, 1024 tiles, one failed rank, Zipf-skewed load): the
+    receive buffer is 15 GB, so row addresses need 64-bit arithmetic and the tile prefix
+    takes several rounds.  Token rows are built on the GPU (row t = row t mod 4096 of a
+    random block, with t stamped into its first two elements) so that the host never holds
+    them all.  Layout compared in full with the oracle; moved rows in full against a torch
+    gather; pack and combine against the oracle on 512 sampled tokens, the ones with the
+    highest and lowest rows included."""
+    T, H, B = 131072, 7168, 4096
+    small = synth.decode_failed_zipf(T=T, H=16)                    # router, placement, mask
+    k, R = small.k, small.R
+    block = synth.decode(T=B, H=H, seed_offset=41).x               # [B, H] bf16 bits
+
+    def host_rows(toks):
+        rows = block[toks % B].copy()
+        rows[:, 0] = toks & 0x3FFF                                 # small finite bf16 patterns
+        rows[:, 1] = toks >> 14
+        return rows
+
+    ctx = binding.Context(num_ranks=R, slots_per_rank=small.S, primary_slots=small.S_prim,
+                          num_logical=small.E, max_tokens=T, topk=k, hidden=H)
+    try:
+        gu.apply_tables(ctx, small.p2l, small.active)
+        x = gu.to_dev(block).repeat(T // B, 1)
+        t_dev = torch.arange(T, device="cuda")
+        x[:, 0] = (t_dev & 0x3FFF).to(torch.int16)
+        x[:, 1] = (t_dev >> 14).to(torch.int16)
+        idx, w = gu.to_dev(small.topk_idx), gu.to_dev(small.topk_w)
+        recv = torch.empty((T * k, H), dtype=torch.int16, device="cuda")
+        out = torch.empty((T, H), dtype=torch.int16, device="cuda")
+        ctx.dispatch_layout(idx, T)
+        ctx.dispatch(x, recv, T)
+        ctx.combine(recv, w, out, T)
+        torch.cuda.synchronize()
+        lay = oracle.step_layout(small.topk_idx, small.p2l, small.active, small.E, R, small.S,
+                                 small.S_prim, 0)
+        got = ctx.read_layout(T)
+        gu.assert_layout_equal(got, lay, T, k)
+        N = got["N"]
+        assert N == T * k and N * H * 2 > 3 * 2 ** 32 and got["rank_count"][13] == 0
+        src_tok = torch.from_numpy(lay["src_of"][:N] // k).cuda().long()
+        assert torch.equal(recv[:N], x.index_select(0, src_tok)), "packed rows"
+        del src_tok
+        rng = np.random.default_rng(12)
+        by_row = np.argsort(lay["row_of"].max(axis=1))
+        toks = np.unique(np.concatenate([rng.choice(T, 448, replace=False), by_row[-32:],
+                                         by_row[:32]]))
+        rows = lay["row_of"][toks]
+        assert rows.max() == N - 1
+        compact = np.arange(rows.size, dtype=np.int32).reshape(rows.shape)
+        y_c = oracle.pack(host_rows(toks), compact)
+        rows_dev = torch.from_numpy(rows.ravel()).cuda().long()
+        assert np.array_equal(gu.to_host(recv.index_select(0, rows_dev), np.uint16), y_c)
+        w_c = small.topk_w[toks]
+        out64 = oracle.combine(y_c, oracle.BF16, w_c, compact)
+        chain = oracle.f32_to_bf16(oracle.combine_chain32(y_c, oracle.BF16, w_c, compact))
+        out_got = gu.to_host(out.index_select(0, torch.from_numpy(toks).cuda().long()), np.uint16)
+        gu.check_combine(out_got, "bf16", out64)
+        assert np.array_equal(out_got, chain)
+    finally:
+        ctx.destroy()
+
+
 @pytest.mark.parametrize("T,H,group", [(256, 1024, 128), (4096, 7168, 128), (64, 1024, 64),
                                        (96, 256, 16)])
 def test_dispatch_with_fused_quantisation(oracle, T, H, group):
