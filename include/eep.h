@@ -96,6 +96,19 @@ typedef struct eep_ctx eep_ctx;
  * On error *out is NULL. */
 int eep_create(const eep_config* cfg, eep_ctx** out);
 
+/* The same context in memory the CALLER owns (say a torch tensor), for callers
+ * that keep all device memory under one allocator: the "stable pointers" of
+ * Fig. 4 / Fig. 8 then lie inside a buffer whose lifetime the caller controls.
+ * eep_workspace_bytes: host only, no GPU needed; *bytes = size the config needs
+ * (same argument checks as eep_create).
+ * eep_create_with_workspace: `workspace` is device memory of the current GPU,
+ * 256-byte aligned, at least that large (checked: EEP_ERR_INVALID_ARG); the
+ * library allocates no device memory, eep_destroy does not free it, and the
+ * caller must keep it alive and untouched until eep_destroy returns. */
+int eep_workspace_bytes(const eep_config* cfg, int64_t* bytes);
+int eep_create_with_workspace(const eep_config* cfg, void* workspace, int64_t workspace_bytes,
+                              eep_ctx** out);
+
 /* A further context of the SAME EP instance as `parent`: it shares parent's
  * membership (the `active` mask -- one peer table per instance, Sec. 4.1) and has
  * its own placement tables, layout arrays and shapes.  This is how the MoE

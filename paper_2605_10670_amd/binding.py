@@ -59,6 +59,8 @@ def load():
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     sig = {
         "eep_create": [ctypes.POINTER(_Config), ctypes.POINTER(vp)],
+        "eep_workspace_bytes": [ctypes.POINTER(_Config), ctypes.POINTER(i64)],
+        "eep_create_with_workspace": [ctypes.POINTER(_Config), vp, i64, ctypes.POINTER(vp)],
         "eep_create_attached": [ctypes.POINTER(_Config), vp, ctypes.POINTER(vp)],
         "eep_destroy": [vp],
         "eep_set_membership": [vp, vp, vp],
@@ -186,6 +188,22 @@ def plan_repair(cur_p2l, active, R, S, S_prim, E, load=None):
                 dram=int(summary[2]), unplaced=int(summary[3]))
 
 
+def workspace_bytes(*, num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk, hidden,
+                    x_dtype="bf16", y_dtype="bf16", out_dtype="bf16", scale_group=None,
+                    policy=SPREAD, strict_coverage=True):
+    """Bytes of device memory a context of this shape needs (host only)."""
+    xd = DTYPES[x_dtype] if isinstance(x_dtype, str) else x_dtype
+    if scale_group is None:
+        scale_group = 128 if xd == FP8_E4M3 else 0
+    cfg = _Config(num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk, hidden,
+                  xd, DTYPES[y_dtype] if isinstance(y_dtype, str) else y_dtype,
+                  DTYPES[out_dtype] if isinstance(out_dtype, str) else out_dtype, scale_group,
+                  policy, 1 if strict_coverage else 0)
+    n = ctypes.c_int64()
+    _check(_library().eep_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)), "eep_workspace_bytes")
+    return n.value
+
+
 def plan_transition(cur_p2l, target_p2l, active, writable, R, S, S_prim, E):
     """Sources for moving to a given target placement (host only); same dict as plan_repair."""
     cur, tgt = (np.ascontiguousarray(a, np.int32) for a in (cur_p2l, target_p2l))
@@ -225,7 +243,7 @@ class Context:
 
     def __init__(self, *, num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk,
                  hidden, x_dtype="bf16", y_dtype="bf16", out_dtype="bf16", scale_group=None,
-                 policy=SPREAD, strict_coverage=True, parent=None):
+                 policy=SPREAD, strict_coverage=True, parent=None, workspace=None):
         xd = DTYPES[x_dtype] if isinstance(x_dtype, str) else x_dtype
         if scale_group is None:
             scale_group = 128 if xd == FP8_E4M3 else 0
@@ -235,7 +253,15 @@ class Context:
                            scale_group, policy, 1 if strict_coverage else 0)
         self._h = ctypes.c_void_p()
         self._parent = parent      # keeps the instance's first context alive
-        if parent is None:
+        self._workspace = workspace    # caller-owned slab (a uint8 device tensor), kept alive
+        if workspace is not None:
+            if parent is not None:
+                raise ValueError("workspace and parent cannot be combined")
+            _check(load().eep_create_with_workspace(ctypes.byref(self.cfg), _ptr(workspace),
+                                                    workspace.numel() * workspace.element_size(),
+                                                    ctypes.byref(self._h)),
+                   "eep_create_with_workspace")
+        elif parent is None:
             _check(load().eep_create(ctypes.byref(self.cfg), ctypes.byref(self._h)), "eep_create")
         else:   # same EP instance: shared membership, own placement and layout
             _check(load().eep_create_attached(ctypes.byref(self.cfg), parent._h,

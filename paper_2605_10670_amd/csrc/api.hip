@@ -37,9 +37,12 @@ int eep_last_hip_error(eep_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
 
 namespace {
 
-int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
-  if (!out) return EEP_ERR_INVALID_ARG;
-  *out = nullptr;
+// One routine behind eep_create, eep_create_attached, eep_create_with_workspace and
+// eep_workspace_bytes (size_only: validate, report the slab size, touch no GPU).
+int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t workspace_bytes,
+                int64_t* size_only, eep_ctx** out) {
+  if (!out && !size_only) return EEP_ERR_INVALID_ARG;
+  if (out) *out = nullptr;
   if (!cfg) return EEP_ERR_INVALID_ARG;
   if (parent && cfg->num_ranks != parent->R) return EEP_ERR_INVALID_ARG;
   const eep_config& f = *cfg;
@@ -95,10 +98,6 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
     return EEP_ERR_INVALID_ARG;
   }
 
-  hipError_t e = hipGetDevice(&c->device);
-  if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
-  if (parent && parent->device != c->device) { delete c; return EEP_ERR_INVALID_ARG; }
-
   const int64_t pairs = (int64_t)c->T_max * c->k;
   int64_t* n = c->field_ints;
   n[EEP_V_ACTIVE] = c->R;
@@ -124,8 +123,36 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
   total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 3 * round_up(1) +
            3 * round_up(c->R) + 4 * round_up(c->P);
-  e = hipMalloc(&c->slab, (size_t)total * sizeof(int32_t));
+  if (size_only) {
+    *size_only = total * (int64_t)sizeof(int32_t);
+    delete c;
+    return EEP_OK;
+  }
+
+  hipError_t e = hipGetDevice(&c->device);
   if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
+  if (parent && parent->device != c->device) { delete c; return EEP_ERR_INVALID_ARG; }
+  if (workspace) {
+    // caller-owned slab: device memory of this GPU, 256-byte aligned, large enough
+    hipPointerAttribute_t at;
+    void* base = nullptr;
+    size_t size = 0;
+    if (((uintptr_t)workspace & 255u) || workspace_bytes < total * (int64_t)sizeof(int32_t) ||
+        hipPointerGetAttributes(&at, workspace) != hipSuccess || at.type != hipMemoryTypeDevice ||
+        at.device != c->device ||
+        hipMemGetAddressRange((hipDeviceptr_t*)&base, &size, (hipDeviceptr_t)workspace) != hipSuccess ||
+        (const char*)workspace + workspace_bytes > (const char*)base + size) {
+      (void)hipGetLastError();
+      delete c;
+      return EEP_ERR_INVALID_ARG;
+    }
+    c->slab = workspace;
+    c->owns_slab = false;
+  } else {
+    e = hipMalloc(&c->slab, (size_t)total * sizeof(int32_t));
+    if (e != hipSuccess) { delete c; return EEP_ERR_HIP; }
+    c->owns_slab = true;
+  }
   int32_t* cur = (int32_t*)c->slab;
   for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) {
     *field_ptr[i] = cur;
@@ -153,7 +180,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
     c->mem = parent->mem;
   } else {
     c->mem = new (std::nothrow) eep_membership();
-    if (!c->mem) { (void)hipFree(c->slab); delete c; return EEP_ERR_INVALID_ARG; }
+    if (!c->mem) { if (c->owns_slab) (void)hipFree(c->slab); delete c; return EEP_ERR_INVALID_ARG; }
     c->mem->R = c->R;
     c->mem->active = c->own_active;
     c->mem->mem_version = c->mem_version_word;
@@ -173,7 +200,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   if (e == hipSuccess) e = launch_fill(c->src_of, -1, pairs, st);
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   if (e != hipSuccess) {
-    (void)hipFree(c->slab);
+    if (c->owns_slab) (void)hipFree(c->slab);
     if (!parent) delete c->mem;
     delete c;
     return EEP_ERR_HIP;
@@ -187,14 +214,31 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
 
 extern "C" {
 
-int eep_create(const eep_config* cfg, eep_ctx** out) { return create_impl(cfg, nullptr, out); }
+int eep_create(const eep_config* cfg, eep_ctx** out) {
+  return create_impl(cfg, nullptr, nullptr, 0, nullptr, out);
+}
+
+int eep_workspace_bytes(const eep_config* cfg, int64_t* bytes) {
+  if (!bytes) return EEP_ERR_INVALID_ARG;
+  *bytes = 0;
+  return create_impl(cfg, nullptr, nullptr, 0, bytes, nullptr);
+}
+
+int eep_create_with_workspace(const eep_config* cfg, void* workspace, int64_t workspace_bytes,
+                              eep_ctx** out) {
+  if (!workspace) {
+    if (out) *out = nullptr;
+    return EEP_ERR_INVALID_ARG;
+  }
+  return create_impl(cfg, nullptr, workspace, workspace_bytes, nullptr, out);
+}
 
 int eep_create_attached(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   if (!parent) {
     if (out) *out = nullptr;
     return EEP_ERR_INVALID_ARG;
   }
-  return create_impl(cfg, parent, out);
+  return create_impl(cfg, parent, nullptr, 0, nullptr, out);
 }
 
 int eep_destroy(eep_ctx* ctx) {
@@ -208,7 +252,7 @@ int eep_destroy(eep_ctx* ctx) {
       m->members.erase(m->members.begin() + i);
       break;
     }
-  hipError_t e2 = hipFree(ctx->slab);
+  hipError_t e2 = ctx->owns_slab ? hipFree(ctx->slab) : hipSuccess;
   if (is_root) delete m;
   delete ctx;
   return (e == hipSuccess && e2 == hipSuccess) ? EEP_OK : EEP_ERR_HIP;

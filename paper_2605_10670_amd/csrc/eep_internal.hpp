@@ -70,6 +70,7 @@ struct eep_ctx {
   int max_tiles;
 
   void* slab;  // the one device allocation everything below points into
+  bool owns_slab;  // false: the caller supplied it (eep_create_with_workspace)
   // tables (fixed addresses, contents patched in place)
   int32_t *active;  // == mem->active
   int32_t *own_active, *mem_version_word;  // slab space used only when this context is the root

@@ -4,6 +4,8 @@ import ctypes
 import os
 import re
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -39,3 +41,20 @@ def test_header_is_plain_c():
         open(src, "w").write('#include "eep.h"\nint main(void){eep_config c; (void)c; return 0;}\n')
         subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
                         "-c", src, "-o", os.path.join(d, "t.o")], check=True)
+
+
+def test_workspace_size_is_host_only_and_checks_the_config():
+    from paper_2605_10670_amd import binding
+    shape = dict(num_ranks=32, slots_per_rank=9, primary_slots=8, num_logical=256, max_tokens=4096,
+                 topk=8, hidden=7168)
+    n = binding.workspace_bytes(**shape)
+    pairs = 4096 * 8
+    assert n % 256 == 0 and n >= 3 * pairs * 4 + 2 * 32 * 288 * 4      # three pair arrays + tile counts
+    assert n < 2 * (3 * pairs * 4 + 3 * 32 * 288 * 4 + 64 * 1024)      # and not much more
+    assert binding.workspace_bytes(**dict(shape, max_tokens=8192)) > n
+    with pytest.raises(binding.EepError) as ei:
+        binding.workspace_bytes(**dict(shape, topk=0))
+    assert ei.value.code == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.EepError) as ei:
+        binding.workspace_bytes(**dict(shape, hidden=7))               # 14-byte rows
+    assert ei.value.code == binding.ERR_ALIGN

@@ -549,3 +549,37 @@ def test_call_order_and_argument_errors():
         binding.Context(num_ranks=2, slots_per_rank=2, primary_slots=1, num_logical=2,
                         max_tokens=4, topk=1, hidden=3)
     assert ei.value.code == binding.ERR_ALIGN
+
+
+def test_context_in_caller_owned_workspace(oracle):
+    """eep_create_with_workspace: the tables and layout arrays live inside a torch tensor."""
+    wl = synth.tiny("a")
+    shape = dict(num_ranks=wl.R, slots_per_rank=wl.S, primary_slots=wl.S_prim, num_logical=wl.E,
+                 max_tokens=wl.T, topk=wl.k, hidden=wl.H, x_dtype=wl.x_dtype, y_dtype=wl.y_dtype,
+                 out_dtype=wl.out_dtype)
+    need = binding.workspace_bytes(**shape)
+    torch.cuda.empty_cache()
+    ws = torch.full((need + 4096,), 0x7F, dtype=torch.uint8, device="cuda")
+    guard = ws[need:].clone()
+    for bad in (ws[:need - 256], ws[1:need + 1],
+                torch.empty(need, dtype=torch.uint8, pin_memory=True)):
+        with pytest.raises(binding.EepError) as ei:
+            binding.Context(workspace=bad, **shape)
+        assert ei.value.code == binding.ERR_INVALID_ARG
+    ctx = binding.Context(workspace=ws[:need], **shape)
+    try:
+        lo, hi = ws.data_ptr(), ws.data_ptr() + need
+        assert all(lo <= p < hi for p in ctx.view_pointers().values())
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        dev = gu.DeviceStep(ctx, wl)
+        dev.step()
+        dev.sync()
+        ref = oracle_step(oracle, wl)
+        gu.assert_layout_equal(ctx.read_layout(wl.T), ref["lay"], wl.T, wl.k)
+        assert np.array_equal(gu.to_host(dev.out, gu.NP_OF[wl.out_dtype]).view(np.uint32),
+                              ref["chain_bits"].view(np.uint32))
+    finally:
+        ctx.destroy()
+    assert torch.equal(ws[need:], guard)                 # nothing written past the stated size
+    ws.fill_(1)                                          # still the caller's memory after destroy
+    torch.cuda.synchronize()
