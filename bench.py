@@ -103,6 +103,10 @@ WORKLOADS = {
     "repair": ("weight movement after a rank failure (eep_apply_repair; not the hot path): 32 ranks "
                "x (8+2) slots, one redundant slot empty, E=256, 44 MB per expert (three 7168x2048 "
                "fp8 matrices), rank 13 fails; backup in pinned host memory"),
+    "repair_scales": ("weight movement vs failure scale (the one-GPU analogue of the paper's recovery "
+                      "breakdown, Sec. 6.3): 32 ranks x (8+8) slots, experts 0-3 of every rank "
+                      "replicated once, four redundant slots per rank empty, E=256, 44 MB per expert; "
+                      "1, 2, 4, 8, 16 failed ranks; backup in pinned host memory"),
 }
 BYTES_OF = {"f32": 4, "bf16": 2, "fp8": 1}
 
@@ -168,6 +172,62 @@ def bench_repair(args, stream, copy_gbs):
     ctx.destroy()
 
 
+def bench_repair_scales(args, stream):
+    """Plan + carry out the repair for 1..16 failed ranks of 32: which tier the weights come
+    from and how long planning (host) and moving (GPU) take."""
+    import numpy as np
+    import torch
+    from paper_2605_10670_amd import binding, synth
+
+    R, S_prim, S_red, E = 32, 8, 8, 256
+    S = S_prim + S_red
+    slot_bytes = 3 * 7168 * 2048
+    pref = synth.preferred_placement(R, S_prim, S_red).reshape(R, S)
+    pref[:, 12:] = -1
+    pref = pref.ravel().copy()
+    order = np.random.default_rng(0).permutation(R)
+    weights = torch.empty((R * S, slot_bytes), dtype=torch.uint8, device="cuda")
+    backup = torch.empty((E, slot_bytes), dtype=torch.uint8, pin_memory=True)
+    ctx = binding.Context(num_ranks=R, slots_per_rank=S, primary_slots=S_prim, num_logical=E,
+                          max_tokens=R, topk=8, hidden=64)
+    rows = []
+    for n_failed in (1, 2, 4, 8, 16):
+        dead = synth.active_mask(R, order[:n_failed])
+        ctx.update_placement(pref, stream)
+        ctx.set_membership(np.ones(R, np.int32), stream)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        plan = binding.plan_repair(pref, dead, R, S, S_prim, E)
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        assert plan["unplaced"] == 0
+        times = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            ctx.apply_repair(weights, backup, slot_bytes, plan, stream)
+            ctx.set_membership(dead, stream)            # placement first, then the mask
+            e1.record(stream)
+            e1.synchronize()
+            times.append(e0.elapsed_time(e1))
+            ctx.set_membership(np.ones(R, np.int32), stream)     # rejoin: mask, then placement
+            ctx.update_placement(pref, stream)
+        move_ms = statistics.median(times)
+        moved = (plan["peer"] + plan["dram"]) * slot_bytes
+        rows.append({"failed_ranks": n_failed, "local": plan["local"], "peer": plan["peer"],
+                     "dram": plan["dram"],
+                     "dram_share": round(plan["dram"] / max(1, plan["dram"] + plan["peer"]), 3),
+                     "plan_ms_host": round(plan_ms, 3), "move_and_publish_ms": round(move_ms, 3),
+                     "moved_mb": round(moved / 1e6, 1),
+                     "moved_gbs": round(moved / (move_ms * 1e-3) / 1e9, 1)})
+    print(json.dumps({
+        "metric": "repair_move_ms_by_failure_scale", "value": rows[0]["move_and_publish_ms"],
+        "unit": "ms", "n_gpus": 1, "steps": 3, "warmup": 0,
+        "ms_per_step": rows[0]["move_and_publish_ms"], "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": WORKLOADS["repair_scales"]}, "scales": rows}))
+    ctx.destroy()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -213,6 +273,8 @@ def main():
 
     if args.workload == "repair":
         return bench_repair(args, stream, copy_gbs)
+    if args.workload == "repair_scales":
+        return bench_repair_scales(args, stream)
 
     quant = args.workload == "decode_quant"
     if args.workload in ("decode", "decode_quant"):
