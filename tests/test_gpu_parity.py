@@ -583,3 +583,48 @@ def test_context_in_caller_owned_workspace(oracle):
     assert torch.equal(ws[need:], guard)                 # nothing written past the stated size
     ws.fill_(1)                                          # still the caller's memory after destroy
     torch.cuda.synchronize()
+
+
+def test_one_context_many_batch_sizes_in_a_row(oracle):
+    """The same context and buffers serve batches of different sizes back to back, crossing
+    between the few-tile and the many-tile layout paths, with a membership change in the
+    middle: nothing left over from a larger earlier batch may leak into a later one."""
+    R, sp, sr, k, H = 32, 8, 1, 8, 256
+    E, T_max = R * sp, 12288                                      # 96 tiles at full size
+    rng = np.random.default_rng(77)
+    pref = synth.preferred_placement(R, sp, sr)
+    failed = (11,)
+    repaired = synth.repaired_placement(pref, failed, R, sp, sr)
+    ctx = binding.Context(num_ranks=R, slots_per_rank=sp + sr, primary_slots=sp, num_logical=E,
+                          max_tokens=T_max, topk=k, hidden=H)
+    try:
+        ctx.update_placement(pref)
+        recv = torch.zeros((T_max * k, H), dtype=torch.int16, device="cuda")
+        out = torch.zeros((T_max, H), dtype=torch.int16, device="cuda")
+        p2l, active = pref, synth.active_mask(R)
+        for step, T in enumerate([12288, 4096, 96, 0, 8192, 32, 12288, 4128]):
+            if step == 4:
+                ctx.update_placement(repaired)
+                ctx.set_membership(synth.active_mask(R, failed))
+                p2l, active = repaired, synth.active_mask(R, failed)
+            x = synth.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+            idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+            if T:
+                x_d, idx_d, w_d = gu.to_dev(x), gu.to_dev(idx), gu.to_dev(w)
+            else:
+                x_d = idx_d = w_d = None
+            ctx.dispatch_layout(idx_d, T)
+            ctx.dispatch(x_d, recv, T)
+            ctx.combine(recv, w_d, out, T)
+            torch.cuda.synchronize()
+            lay = oracle.step_layout(idx, p2l, active, E, R, sp + sr, sp, oracle.SPREAD)
+            gu.assert_layout_equal(ctx.read_layout(T), lay, T, k)
+            if T == 0:
+                continue
+            rows = oracle.pack(x, lay["row_of"])
+            N = lay["N"]
+            assert np.array_equal(gu.to_host(recv[:N], np.uint16), rows[:N]), (step, T)
+            chain = oracle.f32_to_bf16(oracle.combine_chain32(rows, oracle.BF16, w, lay["row_of"]))
+            assert np.array_equal(gu.to_host(out[:T], np.uint16), chain), (step, T)
+    finally:
+        ctx.destroy()
