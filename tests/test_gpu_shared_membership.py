@@ -110,3 +110,56 @@ def test_failure_detected_in_one_layer_drops_the_rank_for_all(oracle):
     finally:
         b.destroy()
         a.destroy()
+
+
+def test_two_contexts_in_flight_on_two_streams(oracle):
+    """Two micro-batches of one layer kept in flight at once: two contexts of one
+    instance (own layout arrays each), each on its own stream, 20 overlapping steps,
+    a table patch half-way.  Both must match the oracle every time."""
+    wl_a, wl_b = synth.decode(T=1024, H=1024, seed_offset=51), synth.decode(T=1024, H=1024,
+                                                                            seed_offset=52)
+    R = wl_a.R
+    failed = (4,)
+    dead, live = synth.active_mask(R, failed), synth.active_mask(R)
+    repaired = synth.repaired_placement(wl_a.p2l, failed, R, wl_a.S_prim, wl_a.S_red)
+    a = gu.make_context(wl_a)
+    b = binding.Context(num_ranks=R, slots_per_rank=wl_b.S, primary_slots=wl_b.S_prim,
+                        num_logical=wl_b.E, max_tokens=wl_b.T, topk=wl_b.k, hidden=wl_b.H,
+                        parent=a)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        a.update_placement(wl_a.p2l)
+        b.update_placement(wl_a.p2l)
+        torch.cuda.synchronize()
+        dev_a, dev_b = gu.DeviceStep(a, wl_a, sa), gu.DeviceStep(b, wl_b, sb)
+        torch.cuda.synchronize()
+
+        def expected(wl, p2l, active):
+            lay = oracle.step_layout(wl.topk_idx, p2l, active, wl.E, R, wl.S, wl.S_prim, 0)
+            recv = oracle.pack(wl.x, lay["row_of"])
+            return lay, oracle.f32_to_bf16(oracle.combine_chain32(recv, oracle.BF16, wl.topk_w,
+                                                                  lay["row_of"]))
+
+        want = {(n, f): expected(wl, repaired if f else wl_a.p2l, dead if f else live)
+                for n, wl in (("a", wl_a), ("b", wl_b)) for f in (False, True)}
+        for step in range(20):
+            down = step >= 10
+            if step == 10:                                  # both layers repaired, then the mask
+                torch.cuda.synchronize()
+                a.update_placement(repaired)
+                b.update_placement(repaired)
+                a.set_membership(dead)
+                torch.cuda.synchronize()
+            dev_a.out.zero_()
+            dev_b.out.zero_()
+            torch.cuda.synchronize()
+            dev_a.step()                                    # queued on sa ...
+            dev_b.step()                                    # ... and on sb, no wait in between
+            torch.cuda.synchronize()
+            for name, ctx, dev, wl in (("a", a, dev_a, wl_a), ("b", b, dev_b, wl_b)):
+                lay, chain = want[(name, down)]
+                gu.assert_layout_equal(ctx.read_layout(wl.T), lay, wl.T, wl.k)
+                assert np.array_equal(gu.to_host(dev.out, np.uint16), chain), (step, name)
+    finally:
+        b.destroy()
+        a.destroy()
