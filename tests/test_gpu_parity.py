@@ -123,8 +123,9 @@ def test_many_tiles_and_odd_rank_counts(oracle, R, T):
     assert got["N"] == T * k
 
 
-def test_masked_repeated_and_out_of_range_indices(oracle):
-    wl = synth.decode(T=256, H=256)
+@pytest.mark.parametrize("T", [96, 256])   # single-workgroup layout / tiled layout
+def test_masked_repeated_and_out_of_range_indices(oracle, T):
+    wl = synth.decode(T=T, H=256)
     rng = np.random.default_rng(5)
     idx = wl.topk_idx.copy()
     idx[rng.random(idx.shape) < 0.05] = -1
@@ -628,3 +629,27 @@ def test_one_context_many_batch_sizes_in_a_row(oracle):
             assert np.array_equal(gu.to_host(out[:T], np.uint16), chain), (step, T)
     finally:
         ctx.destroy()
+
+
+@pytest.mark.parametrize("policy", [binding.SPREAD, binding.FIRST_LIVE])
+@pytest.mark.parametrize("R,T,k,failed", [(32, 128, 8, (13,)), (32, 160, 8, (13,)), (4, 128, 2, ()),
+                                          (8, 40, 20, (2, 5)), (2, 128, 8, ()), (64, 128, 8, (0, 63)),
+                                          (16, 32, 32, (7,)), (1, 128, 8, ())])
+def test_small_batches_around_the_single_workgroup_limit(oracle, policy, R, T, k, failed):
+    """Batches of at most 128 tokens and 1024 pairs are laid out by one workgroup in one
+    launch; just above either limit the tiled path runs.  Both must give the oracle's
+    layout: rank boundaries inside a bitmap word, k up to 32, failed first and last
+    ranks, one rank only."""
+    rng = np.random.default_rng(1000 + R * 7 + T + k)
+    sr, H = 2, 128
+    sp = -(-max(R * 4, k) // R)
+    E = R * sp
+    x = synth.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    pref = synth.preferred_placement(R, sp, sr)
+    p2l = synth.repaired_placement(pref, failed, R, sp, sr) if failed else pref
+    wl = synth.Workload("small", T, H, E, k, R, sp, sr, "bf16", "bf16", "bf16", "identity", failed,
+                        idx, w, x, p2l, synth.active_mask(R, failed))
+    got, _ = run_and_compare(oracle, wl, policy=policy, strict=False)
+    for r in failed:
+        assert got["rank_count"][r] == 0
