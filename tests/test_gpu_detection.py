@@ -28,9 +28,10 @@ def _oracle_out(oracle, wl, p2l, active, drop_rank=None):
     return lay, rows, chain
 
 
+@pytest.mark.parametrize("T_batch", [512, 64])   # tiled layout / single-workgroup layout
 @pytest.mark.parametrize("use_graph", [False, True])
-def test_silent_rank_is_dropped_by_the_kernel(oracle, use_graph):
-    wl = synth.churn_inputs(1, T=512, H=512)[0]
+def test_silent_rank_is_dropped_by_the_kernel(oracle, use_graph, T_batch):
+    wl = synth.churn_inputs(1, T=T_batch, H=512)[0]
     T, k, R = wl.T, wl.k, wl.R
     ctx = gu.make_context(wl)
     stream = torch.cuda.Stream()
