@@ -26,6 +26,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // stores.
 // ---------------------------------------------------------------------------
 constexpr int kPackVecs = 14;
+constexpr int kPackMinWaves = 2048;  // below this many tokens a row is split over wavefronts
 
 __device__ inline void store_through(u32x4* p, u32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
@@ -34,17 +35,21 @@ __device__ inline void store_through(u32x4* p, u32x4 v) {
 // U = 16-byte vectors per lane per pass.  EXACT: the row is a whole number of
 // passes (row_vecs % (64 * U) == 0), so no load or store needs a bounds guard
 // and the compiler keeps all U loads of a pass in flight; otherwise every
-// access is guarded (any row size).
+// access is guarded (any row size).  `parts` wavefronts share a token, taking
+// every parts-th pass each: 1 for large batches (a whole row per wavefront
+// measured fastest there), more for small ones, which would otherwise leave
+// most of the chip idle.
 template <int U, bool EXACT>
 __global__ __launch_bounds__(64) void k_pack(const u32x4* __restrict__ x,
                                              u32x4* __restrict__ recv,
                                              const int32_t* __restrict__ row_of, int k,
-                                             int row_vecs) {
-  const int t = blockIdx.x;
+                                             int row_vecs, int parts) {
+  const int t = blockIdx.x / parts;
+  const int part = blockIdx.x - t * parts;
   const int lane = threadIdx.x;
   const int32_t* rows = row_of + (int64_t)t * k;
   const u32x4* src = x + (int64_t)t * row_vecs;
-  for (int v0 = 0; v0 < row_vecs; v0 += 64 * U) {
+  for (int v0 = part * 64 * U; v0 < row_vecs; v0 += parts * 64 * U) {
     u32x4 buf[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -93,9 +98,10 @@ __global__ __launch_bounds__(64) void k_pack_scales(const u32x4* __restrict__ x_
 
 template <int U, bool EXACT>
 static hipError_t launch_pack_t(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
-                                float* recv_scale, int T, hipStream_t st) {
-  hipLaunchKernelGGL((k_pack<U, EXACT>), dim3(T), dim3(64), 0, st, (const u32x4*)x,
-                     (u32x4*)recv_x, c->row_of, c->k, (int)(c->x_row_bytes / 16));
+                                float* recv_scale, int T, int parts, hipStream_t st) {
+  hipLaunchKernelGGL((k_pack<U, EXACT>), dim3((unsigned)((int64_t)T * parts)), dim3(64), 0, st,
+                     (const u32x4*)x, (u32x4*)recv_x, c->row_of, c->k,
+                     (int)(c->x_row_bytes / 16), parts);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || c->scale_row_bytes == 0) return e;
   hipLaunchKernelGGL(k_pack_scales, dim3(T), dim3(64), 0, st, (const u32x4*)x_scale,
@@ -108,20 +114,25 @@ hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* re
   if (T == 0) return hipSuccess;
   const int row_vecs = (int)(c->x_row_bytes / 16);
   if (row_vecs % 64 == 0) {
-    // the largest pass width <= kPackVecs that divides the row
+    // Pass width: the largest divisor of the per-lane vector count that is <= kPackVecs and,
+    // for batches too small to fill the chip with one wavefront per token, small enough to
+    // give about kPackMinWaves wavefronts (one pass each).
     const int per_lane = row_vecs / 64;
-    int u = kPackVecs;
+    int want_parts = T >= kPackMinWaves ? 1 : (kPackMinWaves + T - 1) / T;
+    if (want_parts > per_lane) want_parts = per_lane;
+    int u = per_lane / want_parts < kPackVecs ? per_lane / want_parts : kPackVecs;
     while (per_lane % u != 0) --u;
+    const int parts = T >= kPackMinWaves ? 1 : per_lane / u;
     switch (u) {
 #define EEP_PACK_CASE(U) \
-  case U: return launch_pack_t<U, true>(c, x, x_scale, recv_x, recv_scale, T, st);
+  case U: return launch_pack_t<U, true>(c, x, x_scale, recv_x, recv_scale, T, parts, st);
       EEP_PACK_CASE(14) EEP_PACK_CASE(13) EEP_PACK_CASE(12) EEP_PACK_CASE(11) EEP_PACK_CASE(10)
       EEP_PACK_CASE(9) EEP_PACK_CASE(8) EEP_PACK_CASE(7) EEP_PACK_CASE(6) EEP_PACK_CASE(5)
       EEP_PACK_CASE(4) EEP_PACK_CASE(3) EEP_PACK_CASE(2) EEP_PACK_CASE(1)
 #undef EEP_PACK_CASE
     }
   }
-  return launch_pack_t<kPackVecs, false>(c, x, x_scale, recv_x, recv_scale, T, st);
+  return launch_pack_t<kPackVecs, false>(c, x, x_scale, recv_x, recv_scale, T, 1, st);
 }
 
 // ---------------------------------------------------------------------------
