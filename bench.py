@@ -240,6 +240,9 @@ def main():
                          "step per MoE layer in a single graph); reduced to a divisor of --steps")
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="decode",
                     help="decode (default) is the configuration the headline metric is quoted on")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="decode workloads only: batch size T (a multiple of 32) instead of 4096, "
+                         "e.g. 32..256 for the low-concurrency decode regime")
     ap.add_argument("--detect", action="store_true",
                     help="switch GPU-side failure detection on (1 s timeout as in the paper): adds "
                          "the signal kernel after dispatch and the bounded wait before combine")
@@ -278,7 +281,7 @@ def main():
 
     quant = args.workload == "decode_quant"
     if args.workload in ("decode", "decode_quant"):
-        wl = synth.decode()
+        wl = synth.decode(T=args.tokens) if args.tokens else synth.decode()
         if quant:   # receive rows are fp8 + scales; the stand-in dequantises them once, untimed
             wl.x_dtype, wl.stub = "fp8", "dequant"
     elif args.workload == "decode_failed_zipf":
@@ -417,7 +420,8 @@ def main():
         kernels[kname] = {"avg_launch_us": launch_ms * 1e3,
                           "algorithmic_bytes_per_launch": nbytes[stage], "achieved": gbs,
                           "frac": gbs / HBM_PEAK_GBS,
-                          "traffic": HBM_TRAFFIC_BYTES.get(kname) if args.workload == "decode"
+                          "traffic": HBM_TRAFFIC_BYTES.get(kname)
+                          if args.workload == "decode" and not args.tokens
                           else None}
     dom = max(kernels, key=lambda n: kernels[n]["avg_launch_us"])
     result = {
@@ -429,7 +433,9 @@ def main():
         "ms_per_step": ms, "us_per_step": ms * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "u8"}[wl.x_dtype], "data": "synthetic",
-        "config": {"workload": WORKLOADS[args.workload], "mode": args.mode,
+        "config": {"workload": WORKLOADS[args.workload] if not args.tokens else
+                   WORKLOADS[args.workload].replace("T=4096 (32 ranks x 128)", f"T={args.tokens}")
+                   .replace("T=4096", f"T={args.tokens}"), "mode": args.mode,
                    "steps_per_graph": spg if args.mode == "graph" else None,
                    "failure_detection": bool(args.detect), "step": "dispatch_layout + dispatch + combine",
                    "algorithmic_bytes_per_step": nbytes["total"]},
