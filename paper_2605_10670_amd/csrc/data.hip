@@ -26,7 +26,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // stores.
 // ---------------------------------------------------------------------------
 constexpr int kPackVecs = 14;
-constexpr int kPackMinWaves = 2048;  // below this many tokens a row is split over wavefronts
+constexpr int kPackSplitBelow = 1024;  // batches below this many tokens split a row over wavefronts
 
 __device__ inline void store_through(u32x4* p, u32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
@@ -114,15 +114,25 @@ hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* re
   if (T == 0) return hipSuccess;
   const int row_vecs = (int)(c->x_row_bytes / 16);
   if (row_vecs % 64 == 0) {
-    // Pass width: the largest divisor of the per-lane vector count that is <= kPackVecs and,
-    // for batches too small to fill the chip with one wavefront per token, small enough to
-    // give about kPackMinWaves wavefronts (one pass each).
+    // Large batches: one wavefront per token, the largest pass width <= kPackVecs that
+    // divides the per-lane vector count (a whole 14 KiB row per wavefront at the decode
+    // shape).  Small batches (< kPackSplitBelow tokens) would leave most of the chip idle
+    // that way, so a row is split over wavefronts, each taking one pass of the smallest
+    // width >= 2: measured at 32 ranks, top-8, 14 KiB rows, 2 KiB per wavefront and row is
+    // about twice as fast as 1 KiB or 7 KiB pieces for 64 <= T <= 256 (1 KiB pieces are
+    // no better than whole rows), and nothing differs from T = 1024 on.
     const int per_lane = row_vecs / 64;
-    int want_parts = T >= kPackMinWaves ? 1 : (kPackMinWaves + T - 1) / T;
-    if (want_parts > per_lane) want_parts = per_lane;
-    int u = per_lane / want_parts < kPackVecs ? per_lane / want_parts : kPackVecs;
-    while (per_lane % u != 0) --u;
-    const int parts = T >= kPackMinWaves ? 1 : per_lane / u;
+    int u, parts;
+    if (T < kPackSplitBelow && per_lane > 1) {
+      u = 2;
+      while (per_lane % u != 0) ++u;  // ends at per_lane at the latest
+      if (u > kPackVecs) u = 1;       // a large prime: fall back to single vectors
+      parts = per_lane / u;
+    } else {
+      u = kPackVecs;
+      while (per_lane % u != 0) --u;
+      parts = 1;
+    }
     switch (u) {
 #define EEP_PACK_CASE(U) \
   case U: return launch_pack_t<U, true>(c, x, x_scale, recv_x, recv_scale, T, parts, st);
