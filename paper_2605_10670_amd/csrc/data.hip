@@ -39,17 +39,20 @@ __device__ inline void store_through(u32x4* p, u32x4 v) {
 // every parts-th pass each: 1 for large batches (a whole row per wavefront
 // measured fastest there), more for small ones, which would otherwise leave
 // most of the chip idle.
-template <int U, bool EXACT>
+// SPLIT selects at compile time: the one-wavefront-per-token form keeps its simpler
+// indexing (2 us faster at the decode shape than the general form with parts = 1).
+template <int U, bool EXACT, bool SPLIT>
 __global__ __launch_bounds__(64) void k_pack(const u32x4* __restrict__ x,
                                              u32x4* __restrict__ recv,
                                              const int32_t* __restrict__ row_of, int k,
                                              int row_vecs, int parts) {
-  const int t = blockIdx.x / parts;
-  const int part = blockIdx.x - t * parts;
+  const int t = SPLIT ? blockIdx.x / parts : blockIdx.x;
+  const int part = SPLIT ? blockIdx.x - t * parts : 0;
+  const int step = SPLIT ? parts * 64 * U : 64 * U;
   const int lane = threadIdx.x;
   const int32_t* rows = row_of + (int64_t)t * k;
   const u32x4* src = x + (int64_t)t * row_vecs;
-  for (int v0 = part * 64 * U; v0 < row_vecs; v0 += parts * 64 * U) {
+  for (int v0 = part * 64 * U; v0 < row_vecs; v0 += step) {
     u32x4 buf[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -99,9 +102,13 @@ __global__ __launch_bounds__(64) void k_pack_scales(const u32x4* __restrict__ x_
 template <int U, bool EXACT>
 static hipError_t launch_pack_t(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
                                 float* recv_scale, int T, int parts, hipStream_t st) {
-  hipLaunchKernelGGL((k_pack<U, EXACT>), dim3((unsigned)((int64_t)T * parts)), dim3(64), 0, st,
-                     (const u32x4*)x, (u32x4*)recv_x, c->row_of, c->k,
-                     (int)(c->x_row_bytes / 16), parts);
+  if (parts > 1)
+    hipLaunchKernelGGL((k_pack<U, EXACT, true>), dim3((unsigned)((int64_t)T * parts)), dim3(64), 0,
+                       st, (const u32x4*)x, (u32x4*)recv_x, c->row_of, c->k,
+                       (int)(c->x_row_bytes / 16), parts);
+  else
+    hipLaunchKernelGGL((k_pack<U, EXACT, false>), dim3(T), dim3(64), 0, st, (const u32x4*)x,
+                       (u32x4*)recv_x, c->row_of, c->k, (int)(c->x_row_bytes / 16), 1);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || c->scale_row_bytes == 0) return e;
   hipLaunchKernelGGL(k_pack_scales, dim3(T), dim3(64), 0, st, (const u32x4*)x_scale,
