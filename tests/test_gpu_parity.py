@@ -163,7 +163,10 @@ def test_dtype_and_topk_matrix(oracle, dtypes, k):
 @pytest.mark.parametrize("shape", [
     dict(R=128, sp=2, sr=1, k=4, T=128 * 16, H=256, xd="bf16"),    # P=384 slots, many ranks
     dict(R=8, sp=8, sr=2, k=32, T=8 * 128, H=128, xd="bf16"),      # k=32: tile pairs > fused limit
-    dict(R=4, sp=4, sr=1, k=3, T=4 * 50, H=8192, xd="bf16"),       # 16 KiB rows: two pack passes
+    dict(R=4, sp=4, sr=1, k=3, T=4 * 50, H=8192, xd="bf16"),       # 16 KiB rows, small batch: split in 2 KiB pieces
+    dict(R=4, sp=4, sr=1, k=3, T=4 * 300, H=8192, xd="bf16"),      # 16 KiB rows, large batch: two passes per wavefront
+    dict(R=4, sp=4, sr=1, k=3, T=4 * 300, H=6656, xd="bf16"),      # 13 vectors per lane, one pass
+    dict(R=4, sp=4, sr=1, k=3, T=4 * 40, H=6656, xd="bf16"),       # 13 is prime: small batch split into single passes of 13
     dict(R=4, sp=4, sr=1, k=5, T=4 * 7, H=5000, xd="f32"),         # 20000-byte fp32 rows, ragged parts
     dict(R=2, sp=1, sr=3, k=2, T=2 * 300, H=8, xd="bf16"),         # 16-byte rows, more replicas than experts
     dict(R=4, sp=2, sr=1, k=4, T=4 * 33, H=4608, xd="bf16"),       # 9 vectors per lane (pass width 9)
