@@ -246,6 +246,10 @@ def main():
     ap.add_argument("--detect", action="store_true",
                     help="switch GPU-side failure detection on (1 s timeout as in the paper): adds "
                          "the signal kernel after dispatch and the bounded wait before combine")
+    ap.add_argument("--isolated", action="store_true",
+                    help="also time dispatch alone and combine alone in loops of their own (out of "
+                         "sequence: inside a step part of what dispatch writes is still draining "
+                         "to HBM while combine runs, so the split between the two differs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--calib", action="store_true",
                     help="first launch 5 plain copy kernels of 512 MiB (k_calibration_copy), the "
@@ -403,6 +407,10 @@ def main():
     per_step = sorted(e[0].elapsed_time(e[3]) * 1e3 for e in ev)
     pct = lambda q: per_step[min(len(per_step) - 1, int(q * len(per_step)))]
     other_ms = time_events(stream, step, args.steps)   # eager steps, no inner events
+    isolated = None
+    if args.isolated:
+        isolated = {"dispatch": time_events(stream, dispatch, args.steps) * 1e3,
+                    "combine": time_events(stream, combine, args.steps) * 1e3}
     if graph is not None:
         graph.destroy()
 
@@ -454,6 +462,8 @@ def main():
                      "avg_launch_us": kernels[dom]["avg_launch_us"]},
         "kernels": kernels,
     }
+    if isolated is not None:
+        result["isolated_us"] = isolated
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, nbytes["total"], quant)
     ctx.destroy()
