@@ -91,6 +91,42 @@ def pack(x, row_of, fill=0):
     return recv
 
 
+def dedup_layout(slot_of, row_of, R, S):
+    """De-duplicated dispatch layout -> dict(dedup_count, dedup_offset, dedup_row, lead, expand_of, N_d)."""
+    slot_of, row_of = _i32(slot_of), _i32(row_of)
+    T, k = slot_of.shape
+    out = dict(dedup_count=np.empty(R, np.int32), dedup_offset=np.empty(R + 1, np.int32),
+               dedup_row=np.empty((T, k), np.int32), lead=np.empty((T, k), np.int32),
+               expand_of=np.empty(T * k, np.int32))
+    seen = np.empty(R, np.int32)
+    lib().eeo_dedup_layout(T, k, R, S, _p(slot_of), _p(row_of), _p(out["dedup_count"]),
+                           _p(out["dedup_offset"]), _p(out["dedup_row"]), _p(out["lead"]),
+                           _p(out["expand_of"]), _p(seen))
+    out["N_d"] = int(out["dedup_offset"][-1])
+    return out
+
+
+def pack_dedup(x, dedup_row, lead, fill=0):
+    """Stage 1: x [T, ...] -> recv_d [T*k, ...] (only the first N_d rows are written)."""
+    x = np.ascontiguousarray(x)
+    dedup_row, lead = _i32(dedup_row), _i32(lead)
+    T, k = dedup_row.shape
+    recv_d = np.full((T * k,) + x.shape[1:], fill, dtype=x.dtype)
+    row_bytes = x[0].nbytes if T else 0
+    lib().eeo_pack_dedup(T, k, ctypes.c_int64(row_bytes), _p(x), _p(dedup_row), _p(lead), _p(recv_d))
+    return recv_d
+
+
+def expand(recv_d, expand_of, N, fill=0):
+    """Stage 2: recv[row] = recv_d[expand_of[row]] for row < N."""
+    recv_d = np.ascontiguousarray(recv_d)
+    expand_of = _i32(expand_of)
+    recv = np.full_like(recv_d, fill)
+    row_bytes = recv_d[0].nbytes if recv_d.shape[0] else 0
+    lib().eeo_expand(int(N), ctypes.c_int64(row_bytes), _p(recv_d), _p(expand_of), _p(recv))
+    return recv
+
+
 def stub_scale(recv, dtype, N, offset, p2l, expert_scale):
     """O7 scalar stub.  recv: [rows, H] float32 (dtype F32) or uint16 bf16 bits (BF16)."""
     recv = np.ascontiguousarray(recv)

@@ -239,6 +239,75 @@ void eeo_pack(int T, int k, int64_t row_bytes, const uint8_t* x, const int32_t* 
     }
 }
 
+/* ---------- de-duplicated dispatch (a data-path variant; the paper leaves
+ * payload placement to prior work, Sec. 4.1) ---------------------------------
+ * One row per (token, destination RANK) instead of one per (token, expert):
+ * when several of a token's experts live on one rank the row travels once and
+ * is expanded on the destination.
+ *   dedup_count[r]  tokens with at least one routed pair on rank r
+ *   dedup_offset    exclusive running sum over ranks; dedup_offset[R] = N_d
+ *   dedup_row[t,j]  row of token t in rank r's part of the de-duplicated buffer,
+ *                   r = slot_of[t,j] / S; token-ascending inside a rank; -1 for
+ *                   pairs that are not routed
+ *   lead[t,j]       1 for the first routed pair (lowest j) of token t on that
+ *                   rank -- the pair that carries the row -- else 0
+ *   expand_of[row]  for every row of the expert-major layout (row_of), the row of
+ *                   the de-duplicated buffer that holds its token; -1 for rows >= N
+ * seen: scratch [R]. */
+void eeo_dedup_layout(int T, int k, int R, int S, const int32_t* slot_of, const int32_t* row_of,
+                      int32_t* dedup_count, int32_t* dedup_offset, int32_t* dedup_row,
+                      int32_t* lead, int32_t* expand_of, int32_t* seen) {
+  for (int r = 0; r < R; ++r) dedup_count[r] = 0;
+  for (int t = 0; t < T; ++t) {
+    for (int r = 0; r < R; ++r) seen[r] = 0;
+    for (int j = 0; j < k; ++j) {
+      int p = slot_of[t * k + j];
+      if (p < 0) continue;
+      if (!seen[p / S]) { seen[p / S] = 1; dedup_count[p / S] += 1; }
+    }
+  }
+  dedup_offset[0] = 0;
+  for (int r = 0; r < R; ++r) dedup_offset[r + 1] = dedup_offset[r] + dedup_count[r];
+  for (int i = 0; i < T * k; ++i) expand_of[i] = -1;
+  /* cursor per rank, tokens ascending */
+  for (int r = 0; r < R; ++r) seen[r] = dedup_offset[r];
+  for (int t = 0; t < T; ++t) {
+    for (int j = 0; j < k; ++j) {
+      int p = slot_of[t * k + j];
+      dedup_row[t * k + j] = -1;
+      lead[t * k + j] = 0;
+      if (p < 0) continue;
+      int r = p / S, first = 1, at = -1;
+      for (int jj = 0; jj < j; ++jj) {
+        int q = slot_of[t * k + jj];
+        if (q >= 0 && q / S == r) { first = 0; at = dedup_row[t * k + jj]; break; }
+      }
+      if (first) at = seen[r]++;
+      dedup_row[t * k + j] = at;
+      lead[t * k + j] = first;
+      expand_of[row_of[t * k + j]] = at;
+    }
+  }
+}
+
+/* stage 1: recv_d[dedup_row[t,j]] = x[t] for the leading pair of every (token, rank) */
+void eeo_pack_dedup(int T, int k, int64_t row_bytes, const uint8_t* x, const int32_t* dedup_row,
+                    const int32_t* lead, uint8_t* recv_d) {
+  for (int t = 0; t < T; ++t)
+    for (int j = 0; j < k; ++j)
+      if (lead[t * k + j])
+        memcpy(recv_d + (int64_t)dedup_row[t * k + j] * row_bytes, x + (int64_t)t * row_bytes,
+               (size_t)row_bytes);
+}
+
+/* stage 2, on the destination: recv[row] = recv_d[expand_of[row]] for rows < N */
+void eeo_expand(int N, int64_t row_bytes, const uint8_t* recv_d, const int32_t* expand_of,
+                uint8_t* recv) {
+  for (int row = 0; row < N; ++row)
+    memcpy(recv + (int64_t)row * row_bytes, recv_d + (int64_t)expand_of[row] * row_bytes,
+           (size_t)row_bytes);
+}
+
 /* ---------- O7: expert stand-ins -------------------------------------------- */
 
 /* Logical expert that owns receive row `row`: the slot whose [offset[p],
