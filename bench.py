@@ -99,6 +99,9 @@ WORKLOADS = {
                     "E=256, top-8, ranks 7 and 20 failed"),
     "decode_quant": ("dsv3-decode with quantise-on-dispatch: T=4096, H=7168, bf16 tokens -> fp8 e4m3 "
                      "+ fp32 scale/128 receive rows (eep_dispatch_quant), bf16 combine, all live"),
+    "decode_dedup": ("dsv3-decode with de-duplicated dispatch: T=4096, H=7168 bf16, one row per (token, "
+                     "destination rank) (eep_dedup_layout + eep_dispatch_dedup); the expert stage is "
+                     "taken to gather through expand_of, y prepared once by eep_expand, untimed"),
     "churn": "qwen3-moe-like: T=2048, H=4096 bf16, E=128, top-8, R=16, 8+1 slots/rank, all live",
     "repair": ("weight movement after a rank failure (eep_apply_repair; not the hot path): 32 ranks "
                "x (8+2) slots, one redundant slot empty, E=256, 44 MB per expert (three 7168x2048 "
@@ -284,7 +287,8 @@ def main():
         return bench_repair_scales(args, stream)
 
     quant = args.workload == "decode_quant"
-    if args.workload in ("decode", "decode_quant"):
+    dedup = args.workload == "decode_dedup"
+    if args.workload in ("decode", "decode_quant", "decode_dedup"):
         wl = synth.decode(T=args.tokens) if args.tokens else synth.decode()
         if quant:   # receive rows are fp8 + scales; the stand-in dequantises them once, untimed
             wl.x_dtype, wl.stub = "fp8", "dequant"
@@ -319,8 +323,8 @@ def main():
     recv_scale = (torch.empty((T * k, H // 128), dtype=torch.float32, device="cuda")
                   if (x_scale is not None or quant) else None)
     # identity expert: y aliases the receive buffer; otherwise the stand-in fills y once, untimed
-    y = recv if wl.stub == "identity" else torch.empty((T * k, H), dtype=tdt[wl.y_dtype],
-                                                       device="cuda")
+    y = (recv if wl.stub == "identity" and not dedup else
+         torch.empty((T * k, H), dtype=tdt[wl.y_dtype], device="cuda"))
     out = torch.empty((T, H), dtype=tdt[wl.out_dtype], device="cuda")
     torch.cuda.synchronize()
     ctx.update_placement(wl.p2l, stream)
@@ -328,9 +332,13 @@ def main():
 
     def layout():
         ctx.dispatch_layout(idx, T, stream)
+        if dedup:
+            ctx.dedup_layout(T, stream)
 
     def dispatch():
-        if quant:
+        if dedup:       # recv holds the rank-major, de-duplicated rows
+            ctx.dispatch_dedup(x, recv, T, stream)
+        elif quant:
             ctx.dispatch_quant(x, recv, recv_scale, T, stream)
         else:
             ctx.dispatch(x, recv, T, x_scale, recv_scale, stream)
@@ -350,12 +358,22 @@ def main():
 
     layout()
     dispatch()
-    if wl.stub != "identity":
+    if dedup:           # expansion on the destination, once, untimed: y = expert-major rows
+        ctx.expand(recv, y, T, stream)
+    elif wl.stub != "identity":
         ctx.expert_stub(wl.stub, recv, y, T, recv_scale=recv_scale, stream=stream)
     elif args.detect:
         ctx.signal_experts_done(stream)
     combine()
     stream.synchronize()
+    dedup_info = None
+    if dedup:           # one row per (token, rank): N_d rows are written instead of N
+        n_d = ctx.read_dedup(T, stream)["N_d"]
+        delta = (n_d - T * k) * H * BYTES_OF[wl.x_dtype]
+        nbytes["dispatch"] += delta
+        nbytes["total"] += delta
+        dedup_info = {"rows_expert_major": T * k, "rows_dedup": n_d,
+                      "expand_us": time_events(stream, lambda: ctx.expand(recv, y, T, stream), 20) * 1e3}
     graph = None
     spg = 1
     if args.mode == "graph":
@@ -415,6 +433,7 @@ def main():
         graph.destroy()
 
     kernel_of = {"dispatch": "k_pack_quant" if quant else "k_pack", "combine": "k_combine"}
+    # (with de-duplication the layout stage holds four launches and the dispatch stage k_pack)
     event_cost_ms = max(0.0, (sum(stage_ms.values()) - other_ms) / 3)
     kernels = {}
     for stage, kname in kernel_of.items():
@@ -464,6 +483,8 @@ def main():
     }
     if isolated is not None:
         result["isolated_us"] = isolated
+    if dedup_info is not None:
+        result["dedup"] = dedup_info
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, nbytes["total"], quant)
     ctx.destroy()

@@ -375,6 +375,42 @@ int eep_apply_repair(eep_ctx* ctx, void* weights, const void* backup, int64_t sl
 /* Outcome per slot of the last eep_apply_repair; synchronises the device. */
 int eep_read_repair_outcome(eep_ctx* ctx, int32_t* outcome_host);
 
+/* ---- De-duplicated dispatch (a data-path variant; Sec. 4.1 leaves payload
+ * placement to prior work) --------------------------------------------------
+ * One row per (token, destination RANK) instead of one per (token, expert): when
+ * several of a token's experts live on one rank, the row crosses the fabric once
+ * and is expanded on the destination.  Not for fp8 payloads (EEP_ERR_INVALID_ARG);
+ * at most 1024 ranks.
+ *   eep_dedup_layout    after eep_dispatch_layout of the same T: rank-major row of
+ *                       every pair (token-ascending inside a rank), which pair
+ *                       carries the row (the token's first on that rank), and for
+ *                       every expert-major row the rank-major row behind it.
+ *   eep_dispatch_dedup  recv_dedup[dedup_row] = x[t], once per (token, rank);
+ *                       recv_dedup: device [T*k, H] x_dtype, the first N_d rows
+ *                       are written (N_d <= N; rank r's rows are
+ *                       [dedup_offset[r], dedup_offset[r+1])).
+ *   eep_expand          on the destination: recv_x[row] = recv_dedup[expand_of[row]]
+ *                       for the N routed rows; the result equals eep_dispatch's.
+ *                       Expert kernels that can gather through expand_of skip it.
+ * Call order violations return EEP_ERR_STATE. */
+int eep_dedup_layout(eep_ctx* ctx, int32_t T, void* stream);
+int eep_dispatch_dedup(eep_ctx* ctx, const void* x, void* recv_dedup, int32_t T, void* stream);
+int eep_expand(eep_ctx* ctx, const void* recv_dedup, void* recv_x, int32_t T, void* stream);
+/* Device arrays of the de-duplicated layout (fixed addresses, context-owned):
+ * dedup_count[R], dedup_offset[R+1], dedup_row[T_max*k] (-1: pair not routed),
+ * dedup_dst[T_max*k] (= dedup_row for the pair that carries the row, else -1),
+ * expand_of[T_max*k] (-1 for rows >= N), status[1] = {N_d}. */
+typedef struct {
+  const int32_t *dedup_count, *dedup_offset, *dedup_row, *dedup_dst, *expand_of, *status;
+} eep_dedup_view;
+typedef enum {
+  EEP_D_COUNT = 0, EEP_D_OFFSET, EEP_D_ROW, EEP_D_DST, EEP_D_EXPAND_OF, EEP_D_STATUS,
+  EEP_D_NUM_FIELDS
+} eep_dedup_field;
+int eep_get_dedup_view(eep_ctx* ctx, eep_dedup_view* out);
+/* Copies the first n ints of a field to the host after synchronising `stream`. */
+int eep_read_dedup(eep_ctx* ctx, int32_t field, int32_t* host_dst, int64_t n, void* stream);
+
 /* ---- hipGraph helper (Sec. 2.3, Fig. 4: capture once, replay, patch table
  * contents only) ------------------------------------------------------------
  * eep_graph_begin puts `stream` (not the default stream) into capture mode;

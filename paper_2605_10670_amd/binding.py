@@ -81,6 +81,11 @@ def load():
         "eep_plan_transition": [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp],
         "eep_apply_repair": [vp, vp, vp, i64, vp, vp, vp, vp],
         "eep_read_repair_outcome": [vp, vp],
+        "eep_dedup_layout": [vp, i32, vp],
+        "eep_dispatch_dedup": [vp, vp, vp, i32, vp],
+        "eep_expand": [vp, vp, vp, i32, vp],
+        "eep_get_dedup_view": [vp, vp],
+        "eep_read_dedup": [vp, i32, vp, i64, vp],
         "eep_set_detection": [vp, i64],
         "eep_signal_experts_done": [vp, vp],
         "eep_debug_withhold_signal": [vp, vp, vp],
@@ -370,6 +375,32 @@ class Context:
             rank_offset=self.read("rank_offset", R + 1),
             cnt_src=self.read("cnt_src", R * P).reshape(R, P),
             N=int(st[0]), n_uncovered=int(st[1]), n_masked=int(st[2]), version=int(st[3]))
+
+    # -- de-duplicated dispatch ------------------------------------------------
+    def dedup_layout(self, T, stream=None):
+        _check(load().eep_dedup_layout(self._h, T, _stream(stream)), "eep_dedup_layout", self._h)
+
+    def dispatch_dedup(self, x, recv_dedup, T, stream=None):
+        _check(load().eep_dispatch_dedup(self._h, _ptr(x), _ptr(recv_dedup), T, _stream(stream)),
+               "eep_dispatch_dedup", self._h)
+
+    def expand(self, recv_dedup, recv_x, T, stream=None):
+        _check(load().eep_expand(self._h, _ptr(recv_dedup), _ptr(recv_x), T, _stream(stream)),
+               "eep_expand", self._h)
+
+    def read_dedup(self, T, stream=None):
+        fields = ["dedup_count", "dedup_offset", "dedup_row", "dedup_dst", "expand_of", "status"]
+        sizes = [self.R, self.R + 1, T * self.k, T * self.k, T * self.k, 1]
+        out = {}
+        for i, (name, n) in enumerate(zip(fields, sizes)):
+            a = np.zeros(n, np.int32)
+            _check(load().eep_read_dedup(self._h, i, a.ctypes.data, n, _stream(stream)),
+                   "eep_read_dedup", self._h)
+            out[name] = a
+        out["dedup_row"] = out["dedup_row"].reshape(T, self.k)
+        out["dedup_dst"] = out["dedup_dst"].reshape(T, self.k)
+        out["N_d"] = int(out.pop("status")[0])
+        return out
 
     # -- graphs --------------------------------------------------------------
     def graph_begin(self, stream):

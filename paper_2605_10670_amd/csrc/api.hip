@@ -123,6 +123,9 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
   total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 3 * round_up(1) +
            3 * round_up(c->R) + 4 * round_up(c->P);
+  const int64_t n_dd_tile = (int64_t)c->max_tiles * c->R;
+  total += 3 * round_up(pairs > 0 ? pairs : 1) + round_up(c->R) + round_up(c->R + 1) +
+           round_up(n_dd_tile) + round_up(1);
   if (size_only) {
     *size_only = total * (int64_t)sizeof(int32_t);
     delete c;
@@ -171,7 +174,15 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   c->mv_dst = cur;      cur += round_up(c->P);
   c->mv_src = cur;      cur += round_up(c->P);
   c->mv_expert = cur;   cur += round_up(c->P);
-  c->mv_outcome = cur;
+  c->mv_outcome = cur;  cur += round_up(c->P);
+  c->dd_row = cur;      cur += round_up(pairs > 0 ? pairs : 1);
+  c->dd_dst = cur;      cur += round_up(pairs > 0 ? pairs : 1);
+  c->dd_expand = cur;   cur += round_up(pairs > 0 ? pairs : 1);
+  c->dd_count = cur;    cur += round_up(c->R);
+  c->dd_offset = cur;   cur += round_up(c->R + 1);
+  c->dd_tile = cur;     cur += round_up(n_dd_tile);
+  c->dd_status = cur;
+  c->dedup_T = -1;
   c->detect_timeout_ticks = 0;
   c->wall_clock_khz = 0;
 
@@ -427,6 +438,62 @@ int eep_read_failures(eep_ctx* c, int32_t* failed_host, void* stream) {
     e = launch_fill(c->report, 0, c->R, st);
     if (e != hipSuccess) return fail_hip(c, e);
   }
+  return EEP_OK;
+}
+
+int eep_dedup_layout(eep_ctx* c, int32_t T, void* stream) {
+  if (!c || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;
+  if (c->R > kDedupMaxRanks) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T) return EEP_ERR_STATE;
+  hipError_t e = launch_dedup_layout(c, T, (hipStream_t)stream);
+  if (e != hipSuccess) return fail_hip(c, e);
+  c->dedup_T = T;
+  return EEP_OK;
+}
+
+int eep_dispatch_dedup(eep_ctx* c, const void* x, void* recv_dedup, int32_t T, void* stream) {
+  if (!c || T < 0 || T > c->T_max || c->cfg.x_dtype == EEP_FP8_E4M3) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T || c->dedup_T != T) return EEP_ERR_STATE;
+  if (T == 0) return EEP_OK;
+  if (!x || !recv_dedup) return EEP_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(recv_dedup)) return EEP_ERR_ALIGN;
+  hipError_t e = launch_pack_rows(c, c->dd_dst, x, recv_dedup, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_expand(eep_ctx* c, const void* recv_dedup, void* recv_x, int32_t T, void* stream) {
+  if (!c || T < 0 || T > c->T_max || c->cfg.x_dtype == EEP_FP8_E4M3) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T || c->dedup_T != T) return EEP_ERR_STATE;
+  if (T == 0) return EEP_OK;
+  if (!recv_dedup || !recv_x || recv_dedup == recv_x) return EEP_ERR_INVALID_ARG;
+  if (!aligned16(recv_dedup) || !aligned16(recv_x)) return EEP_ERR_ALIGN;
+  hipError_t e = launch_expand(c, recv_dedup, recv_x, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_read_dedup(eep_ctx* c, int32_t field, int32_t* host_dst, int64_t n, void* stream) {
+  if (!c || field < 0 || field >= EEP_D_NUM_FIELDS || n < 0) return EEP_ERR_INVALID_ARG;
+  const int64_t pairs = (int64_t)c->T_max * c->k;
+  const int64_t size[EEP_D_NUM_FIELDS] = {c->R, c->R + 1, pairs, pairs, pairs, 1};
+  const int32_t* src[EEP_D_NUM_FIELDS] = {c->dd_count, c->dd_offset, c->dd_row,
+                                          c->dd_dst,   c->dd_expand, c->dd_status};
+  if (n > size[field]) return EEP_ERR_INVALID_ARG;
+  if (n == 0) return EEP_OK;
+  if (!host_dst) return EEP_ERR_INVALID_ARG;
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e == hipSuccess)
+    e = hipMemcpy(host_dst, src[field], (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_get_dedup_view(eep_ctx* c, eep_dedup_view* out) {
+  if (!c || !out) return EEP_ERR_INVALID_ARG;
+  out->dedup_count = c->dd_count;
+  out->dedup_offset = c->dd_offset;
+  out->dedup_row = c->dd_row;
+  out->dedup_dst = c->dd_dst;
+  out->expand_of = c->dd_expand;
+  out->status = c->dd_status;
   return EEP_OK;
 }
 

@@ -100,24 +100,25 @@ __global__ __launch_bounds__(64) void k_pack_scales(const u32x4* __restrict__ x_
 }
 
 template <int U, bool EXACT>
-static hipError_t launch_pack_t(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
-                                float* recv_scale, int T, int parts, hipStream_t st) {
+static hipError_t launch_pack_t(eep_ctx* c, const int32_t* rows, const void* x, const float* x_scale,
+                                void* recv_x, float* recv_scale, int T, int parts, hipStream_t st) {
   if (parts > 1)
     hipLaunchKernelGGL((k_pack<U, EXACT, true>), dim3((unsigned)((int64_t)T * parts)), dim3(64), 0,
-                       st, (const u32x4*)x, (u32x4*)recv_x, c->row_of, c->k,
+                       st, (const u32x4*)x, (u32x4*)recv_x, rows, c->k,
                        (int)(c->x_row_bytes / 16), parts);
   else
     hipLaunchKernelGGL((k_pack<U, EXACT, false>), dim3(T), dim3(64), 0, st, (const u32x4*)x,
-                       (u32x4*)recv_x, c->row_of, c->k, (int)(c->x_row_bytes / 16), 1);
+                       (u32x4*)recv_x, rows, c->k, (int)(c->x_row_bytes / 16), 1);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || c->scale_row_bytes == 0) return e;
+  if (e != hipSuccess || x_scale == nullptr) return e;
   hipLaunchKernelGGL(k_pack_scales, dim3(T), dim3(64), 0, st, (const u32x4*)x_scale,
                      (u32x4*)recv_scale, c->row_of, c->k, (int)(c->scale_row_bytes / 16));
   return hipGetLastError();
 }
 
-hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
-                       float* recv_scale, int T, hipStream_t st) {
+static hipError_t launch_pack_any(eep_ctx* c, const int32_t* rows, const void* x,
+                                  const float* x_scale, void* recv_x, float* recv_scale, int T,
+                                  hipStream_t st) {
   if (T == 0) return hipSuccess;
   const int row_vecs = (int)(c->x_row_bytes / 16);
   if (row_vecs % 64 == 0) {
@@ -142,14 +143,60 @@ hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* re
     }
     switch (u) {
 #define EEP_PACK_CASE(U) \
-  case U: return launch_pack_t<U, true>(c, x, x_scale, recv_x, recv_scale, T, parts, st);
+  case U: return launch_pack_t<U, true>(c, rows, x, x_scale, recv_x, recv_scale, T, parts, st);
       EEP_PACK_CASE(14) EEP_PACK_CASE(13) EEP_PACK_CASE(12) EEP_PACK_CASE(11) EEP_PACK_CASE(10)
       EEP_PACK_CASE(9) EEP_PACK_CASE(8) EEP_PACK_CASE(7) EEP_PACK_CASE(6) EEP_PACK_CASE(5)
       EEP_PACK_CASE(4) EEP_PACK_CASE(3) EEP_PACK_CASE(2) EEP_PACK_CASE(1)
 #undef EEP_PACK_CASE
     }
   }
-  return launch_pack_t<kPackVecs, false>(c, x, x_scale, recv_x, recv_scale, T, 1, st);
+  return launch_pack_t<kPackVecs, false>(c, rows, x, x_scale, recv_x, recv_scale, T, 1, st);
+}
+
+hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
+                       float* recv_scale, int T, hipStream_t st) {
+  return launch_pack_any(c, c->row_of, x, x_scale, recv_x, recv_scale, T, st);
+}
+
+hipError_t launch_pack_rows(eep_ctx* c, const int32_t* rows, const void* x, void* recv, int T,
+                            hipStream_t st) {
+  return launch_pack_any(c, rows, x, nullptr, recv, nullptr, T, st);
+}
+
+// ---------------------------------------------------------------------------
+// Expansion on the destination of a de-duplicated dispatch:
+// recv[row] = recv_d[expand_of[row]] for the N routed rows.  One wavefront per
+// row; the grid covers T*k rows and reads N from device memory.
+// ---------------------------------------------------------------------------
+constexpr int kExpandVecs = 7;
+
+__global__ __launch_bounds__(64) void k_expand(const u32x4* __restrict__ recv_d,
+                                               u32x4* __restrict__ recv,
+                                               const int32_t* __restrict__ expand_of,
+                                               const int32_t* __restrict__ status, int row_vecs) {
+  const int row = blockIdx.x;
+  if (row >= status[0]) return;
+  const int from = expand_of[row];
+  if (from < 0) return;
+  const u32x4* src = recv_d + (int64_t)from * row_vecs;
+  u32x4* dst = recv + (int64_t)row * row_vecs;
+  for (int v0 = threadIdx.x; v0 < row_vecs; v0 += 64 * kExpandVecs) {
+    u32x4 buf[kExpandVecs];
+#pragma unroll
+    for (int u = 0; u < kExpandVecs; ++u)
+      if (v0 + u * 64 < row_vecs) buf[u] = __builtin_nontemporal_load(&src[v0 + u * 64]);
+#pragma unroll
+    for (int u = 0; u < kExpandVecs; ++u)
+      if (v0 + u * 64 < row_vecs) store_through(&dst[v0 + u * 64], buf[u]);
+  }
+}
+
+hipError_t launch_expand(eep_ctx* c, const void* recv_dedup, void* recv_x, int T, hipStream_t st) {
+  const int64_t rows = (int64_t)T * c->k;
+  if (rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_expand, dim3((unsigned)rows), dim3(64), 0, st, (const u32x4*)recv_dedup,
+                     (u32x4*)recv_x, c->dd_expand, c->status, (int)(c->x_row_bytes / 16));
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

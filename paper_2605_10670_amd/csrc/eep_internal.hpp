@@ -15,6 +15,7 @@ namespace eep {
 constexpr int kTileTokens = 128;
 constexpr int kBitmapWords = kTileTokens / 32;
 constexpr int kMaxTopk = 32;
+constexpr int kDedupMaxRanks = 1024;  // the de-duplicated layout keeps per-rank bitmaps in LDS
 constexpr int kPatchInts = 512;  // ints carried by value in one table-patch launch
 
 struct Tiling {
@@ -86,6 +87,12 @@ struct eep_ctx {
   // repair batch: destination slot, source slot (-1 = backup), logical expert of
   // each move, and what the relocation kernel did per slot
   int32_t *mv_dst, *mv_src, *mv_expert, *mv_outcome;
+  // de-duplicated dispatch: per pair the row in the rank-major buffer (dd_row), the same
+  // but -1 unless the pair carries the row (dd_dst: what the pack kernel reads), the row of
+  // the rank-major buffer behind every expert-major row (dd_expand), per-rank counts and
+  // offsets, per-tile per-rank counts, {N_d}
+  int32_t *dd_row, *dd_dst, *dd_expand, *dd_count, *dd_offset, *dd_tile, *dd_status;
+  int dedup_T;  // T of the last eep_dedup_layout, -1 if none
   int64_t detect_timeout_ticks;  // 0 = detection off
   int wall_clock_khz;
 
@@ -108,6 +115,11 @@ hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t
 // data.hip
 hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
                        float* recv_scale, int T, hipStream_t st);
+// pack through another row table (the de-duplicated dispatch's), payload rows only
+hipError_t launch_pack_rows(eep_ctx* c, const int32_t* rows, const void* x, void* recv, int T,
+                            hipStream_t st);
+hipError_t launch_expand(eep_ctx* c, const void* recv_dedup, void* recv_x, int T, hipStream_t st);
+hipError_t launch_dedup_layout(eep_ctx* c, int T, hipStream_t st);
 hipError_t launch_pack_quant(eep_ctx* c, const void* x_bf16, void* recv_q, float* recv_scale, int T,
                              hipStream_t st);
 hipError_t launch_combine(eep_ctx* c, const void* y, const float* w, void* out, int T,

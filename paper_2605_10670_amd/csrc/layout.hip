@@ -616,6 +616,158 @@ __global__ __launch_bounds__(256) void k_empty_step(
   }
 }
 
+// ---------------------------------------------------------------------------
+// De-duplicated dispatch (a data-path variant): one row per (token, destination
+// rank).  Two launches after the ordinary layout, built like it: per tile a
+// token bitmap per RANK gives the tile's count and the stable rank of a token
+// inside the tile; then every workgroup derives the rank offsets and the pairs
+// of earlier tiles from the small [tiles][R] count matrix.
+//   dd_row[t,j]  row of token t in rank r's part of the rank-major buffer
+//   dd_dst[t,j]  the same for the pair that carries the row (lowest j on that
+//                rank), -1 for the others: the row table the pack kernel reads
+//   dd_expand[row] for every expert-major row, the rank-major row behind it
+// ---------------------------------------------------------------------------
+template <int KC>
+__global__ __launch_bounds__(kMapThreads) void k_dedup_count(
+    const int32_t* __restrict__ slot_of, int32_t* __restrict__ dd_row,
+    int32_t* __restrict__ dd_dst, int32_t* __restrict__ dd_tile, int k_rt, int R, int S,
+    int tokens_per_rank, int tiles_per_rank, int tile_tokens) {
+  const int k = KC > 0 ? KC : k_rt;
+  extern __shared__ int32_t smem[];
+  uint32_t* s_bm = (uint32_t*)smem;                       // [R][kBitmapWords]
+  int32_t* s_slot = smem + R * kBitmapWords;              // [tile_tokens*k]
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x;
+  const TileRange tr = tile_range(b, tokens_per_rank, tiles_per_rank, tile_tokens);
+  const int npairs = tr.ntok * k;
+  const int64_t g0 = (int64_t)tr.t0 * k;
+  for (int i = tid; i < npairs; i += kMapThreads) s_slot[i] = slot_of[g0 + i];
+  for (int i = tid; i < R * kBitmapWords; i += kMapThreads) s_bm[i] = 0u;
+  __syncthreads();
+  for (int i = tid; i < npairs; i += kMapThreads) {
+    const int p = s_slot[i];
+    if (p >= 0) {
+      const int tl = i / k;
+      atomicOr(&s_bm[(p / S) * kBitmapWords + (tl >> 5)], 1u << (tl & 31));
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < npairs; i += kMapThreads) {
+    const int p = s_slot[i];
+    int rank = -1, lead = 0;
+    if (p >= 0) {
+      const int r = p / S;
+      const int tl = i / k;
+      const int j = i - tl * k;
+      lead = 1;
+      for (int jj = 0; jj < j; ++jj) {
+        const int q = s_slot[tl * k + jj];
+        if (q >= 0 && q / S == r) lead = 0;
+      }
+      const uint32_t* bm = &s_bm[r * kBitmapWords];
+      const int w = tl >> 5;
+      rank = __popc(bm[w] & ((1u << (tl & 31)) - 1u));
+      for (int ww = 0; ww < w; ++ww) rank += __popc(bm[ww]);
+    }
+    dd_row[g0 + i] = rank;  // rank inside the tile; the position kernel turns it into the row
+    dd_dst[g0 + i] = lead;
+  }
+  for (int r = tid; r < R; r += kMapThreads) {
+    int c = 0;
+#pragma unroll
+    for (int w = 0; w < kBitmapWords; ++w) c += __popc(s_bm[r * kBitmapWords + w]);
+    dd_tile[(int64_t)b * R + r] = c;
+  }
+}
+
+template <int KC>
+__global__ __launch_bounds__(kMapThreads) void k_dedup_position(
+    const int32_t* __restrict__ slot_of, const int32_t* __restrict__ row_of,
+    const int32_t* __restrict__ status, const int32_t* __restrict__ dd_tile,
+    int32_t* __restrict__ dd_row, int32_t* __restrict__ dd_dst, int32_t* __restrict__ dd_expand,
+    int32_t* __restrict__ dd_count, int32_t* __restrict__ dd_offset,
+    int32_t* __restrict__ dd_status, int k_rt, int R, int S, int num_tiles, int tokens_per_rank,
+    int tiles_per_rank, int tile_tokens) {
+  const int k = KC > 0 ? KC : k_rt;
+  extern __shared__ int32_t smem[];
+  int32_t* s_cnt = smem;           // [R]   tokens per rank, all tiles
+  int32_t* s_off = s_cnt + R;      // [R+1] exclusive scan of s_cnt
+  int32_t* s_pre = s_off + R + 1;  // [R]   tokens per rank in tiles before this one
+  __shared__ int32_t s_wave[kMapThreads / 64];
+  const int tid = threadIdx.x;
+  const int b = blockIdx.x;
+  const TileRange tr = tile_range(b, tokens_per_rank, tiles_per_rank, tile_tokens);
+  const int npairs = tr.ntok * k;
+  const int64_t g0 = (int64_t)tr.t0 * k;
+  const int N = status[0];
+  for (int r = tid; r < R; r += kMapThreads) {
+    int total = 0, before = 0;
+    for (int tb = 0; tb < num_tiles; tb += kTileBatch) {
+      int v[kTileBatch];
+#pragma unroll
+      for (int u = 0; u < kTileBatch; ++u)
+        v[u] = tb + u < num_tiles ? dd_tile[(int64_t)(tb + u) * R + r] : 0;
+#pragma unroll
+      for (int u = 0; u < kTileBatch; ++u) {
+        total += v[u];
+        before += tb + u < b ? v[u] : 0;
+      }
+    }
+    s_cnt[r] = total;
+    s_pre[r] = before;
+  }
+  __syncthreads();
+  block_exclusive_scan<kMapThreads>(s_cnt, s_off, s_wave, R);
+  for (int i = tid; i < npairs; i += kMapThreads) {
+    const int p = slot_of[g0 + i];
+    int row_d = -1, dst = -1;
+    if (p >= 0) {
+      const int r = p / S;
+      row_d = s_off[r] + s_pre[r] + dd_row[g0 + i];
+      if (dd_dst[g0 + i] != 0) dst = row_d;
+      const int row = row_of[g0 + i];
+      if (row >= 0) dd_expand[row] = row_d;  // (a row withdrawn by failure detection stays -1)
+    }
+    dd_row[g0 + i] = row_d;
+    dd_dst[g0 + i] = dst;
+    if (g0 + i >= N) dd_expand[g0 + i] = -1;  // rows past the last routed pair
+  }
+  if (b == 0) {
+    for (int r = tid; r <= R; r += kMapThreads) {
+      dd_offset[r] = s_off[r];
+      if (r < R) dd_count[r] = s_cnt[r];
+    }
+    if (tid == 0) dd_status[0] = s_off[R];
+  }
+}
+
+hipError_t launch_dedup_layout(eep_ctx* c, int T, hipStream_t st) {
+  Tiling g = make_tiling(T, c->R);
+  if (g.num_tiles == 0) {
+    hipError_t e = launch_fill(c->dd_count, 0, c->R, st);
+    if (e == hipSuccess) e = launch_fill(c->dd_offset, 0, c->R + 1, st);
+    if (e == hipSuccess) e = launch_fill(c->dd_status, 0, 1, st);
+    return e;
+  }
+  const bool k8 = c->k == 8;
+  {
+    size_t lds = sizeof(int32_t) * ((size_t)c->R * kBitmapWords + (size_t)g.tile_tokens * c->k);
+    auto kern = k8 ? k_dedup_count<8> : k_dedup_count<0>;
+    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kMapThreads), lds, st, c->slot_of, c->dd_row,
+                       c->dd_dst, c->dd_tile, c->k, c->R, c->S, g.tokens_per_rank,
+                       g.tiles_per_rank, g.tile_tokens);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  size_t lds = sizeof(int32_t) * ((size_t)3 * c->R + 1);
+  auto kern = k8 ? k_dedup_position<8> : k_dedup_position<0>;
+  hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kMapThreads), lds, st, c->slot_of, c->row_of,
+                     c->status, c->dd_tile, c->dd_row, c->dd_dst, c->dd_expand, c->dd_count,
+                     c->dd_offset, c->dd_status, c->k, c->R, c->S, g.num_tiles, g.tokens_per_rank,
+                     g.tiles_per_rank, g.tile_tokens);
+  return hipGetLastError();
+}
+
 hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st) {
   Tiling g = make_tiling(T, c->R);
   const bool k8 = c->k == 8;
