@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
 # scaled by the same counter's reading for the 512 MiB k_calibration_copy
 # (profiles/dsv3_decode_hbm_traffic.md).
-HBM_TRAFFIC_BYTES = {"k_pack": 59273182 + 469762048, "k_combine": 474009687 + 58720256}
+HBM_TRAFFIC_BYTES = {"k_pack": 59259849 + 469762048, "k_combine": 474030997 + 58720256}
 
 
 def algorithmic_bytes(T, k, H, x_bytes, y_bytes, out_bytes, scale_row_bytes=0):
@@ -396,6 +396,20 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
+    # distribution over individually timed replays (an event pair around each)
+    replay_pct = None
+    if graph is not None:
+        n_rep = max(200, args.steps // spg)
+        rev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_rep)]
+        for e in rev:
+            e[0].record(stream)
+            run()
+            e[1].record(stream)
+        stream.synchronize()
+        per = sorted(e[0].elapsed_time(e[1]) * 1e3 / spg for e in rev)
+        replay_pct = {"replays": n_rep, "p10": per[n_rep // 10], "p50": per[n_rep // 2],
+                      "p90": per[(n_rep * 9) // 10]}
+
     # Per-call durations inside whole steps (eager launches, HIP events recorded on
     # the launch stream between the calls), so that every launch of a kernel in
     # this process happens in the same context: after the previous stage of a step.
@@ -472,6 +486,7 @@ def main():
         "frac_of_copy_ceiling": nbytes["total"] / (ms * 1e-3) / 1e9 / copy_gbs,
         "stages_us": {n: v * 1e3 for n, v in stage_ms.items()},
         "event_gap_us": event_gap_ms * 1e3, "event_cost_in_sequence_us": event_cost_ms * 1e3,
+        "graph_replay_us_per_step": replay_pct,
         "eager_us_per_step": other_ms * 1e3,
         "eager_step_with_events_us": {"p10": pct(0.10), "p50": pct(0.50), "p90": pct(0.90)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved"],
