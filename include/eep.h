@@ -285,7 +285,7 @@ int eep_host_uncovered_experts(int32_t P, int32_t E, int32_t S, const int32_t* p
                                const int32_t* active);
 /* How eep_dispatch_layout tiles T tokens of R source ranks:
  * out = {tokens per rank, tiles per rank, tokens per tile (<= 128), tiles}.
- * (Batches of at most 128 tokens and 1024 pairs are laid out by a single
+ * (Batches of at most 192 tokens and 1536 pairs are laid out by a single
  * workgroup without tiles; the results are the same.) */
 int eep_host_tiling(int32_t T, int32_t R, int32_t out[4]);
 

@@ -321,20 +321,20 @@ __global__ __launch_bounds__(kFusedThreads) void k_scan_position(
 }
 
 // ---------------------------------------------------------------------------
-// Small batches (T <= 128 tokens and T*k <= 1024 pairs: a few tokens per rank,
+// Small batches (T <= 192 tokens and T*k <= 1536 pairs: a few tokens per rank,
 // the low-concurrency decode regime): ONE workgroup does the whole layout in one
 // launch -- map, count, scan and position -- with a token bitmap per slot that
 // spans the whole batch.  No tiles, no second kernel.  Measured at 32 ranks,
 // top-8: the step drops from 17.3 / 18.8 / 22.7 us to 14.5 / 16.0 / 20.1 us at
-// T = 32 / 64 / 128; from 2 pairs per thread on, the tiled two-launch path is
-// as fast or faster, hence the limits.
+// T = 32 / 64 / 128, and by 0.7 us at T = 160 and 192; from 2 pairs per thread
+// on, the tiled two-launch path is as fast or faster, hence the limits.
 // ---------------------------------------------------------------------------
-constexpr int kSmallTokens = 128;
-constexpr int kSmallPairs = 1024;
+constexpr int kSmallTokens = 192;
+constexpr int kSmallPairs = 1536;
 
 inline size_t small_lds_bytes(int E, int P, int R, int T, int k) {
-  const int words = (T + 31) / 32;
-  return sizeof(int32_t) * ((size_t)(E + 1) + P + R + E + P + P + (P + 1) + (size_t)P * words +
+  const int stride = ((T + 31) / 32) | 1;  // odd LDS row stride of the bitmaps
+  return sizeof(int32_t) * ((size_t)(E + 1) + P + R + E + P + P + (P + 1) + (size_t)P * stride +
                             (size_t)2 * T * k);
 }
 
@@ -363,6 +363,7 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
     int P, int T, int tokens_per_rank, int policy) {
   const int k = KC > 0 ? KC : k_rt;
   const int words = (T + 31) >> 5;
+  const int stride = words | 1;  // odd: lanes on different slots reading the same word index hit different banks
   const int npairs = T * k;
   extern __shared__ int32_t smem[];
   int32_t* s_off = smem;                              // [E+1] replica-list starts (CSR)
@@ -372,8 +373,8 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
   int32_t* s_live = s_nlive + E;                      // [P] live replicas, compacted per expert
   int32_t* s_count = s_live + P;                      // [P] pairs per slot
   int32_t* s_offset = s_count + P;                    // [P+1] exclusive scan of s_count
-  uint32_t* s_bm = (uint32_t*)(s_offset + P + 1);     // [P][words] token bitmap per slot
-  int32_t* s_idx = (int32_t*)(s_bm + P * words);      // [T*k] router indices
+  uint32_t* s_bm = (uint32_t*)(s_offset + P + 1);     // [P][stride] token bitmap per slot
+  int32_t* s_idx = (int32_t*)(s_bm + P * stride);     // [T*k] router indices
   int32_t* s_slot = s_idx + npairs;                   // [T*k] chosen slots
   __shared__ int32_t s_drop[2];
   __shared__ int32_t s_wave[kMapThreads / 64];
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
   for (int i = tid; i < P; i += kMapThreads) s_list[i] = l2p_list[i];
   for (int i = tid; i < R; i += kMapThreads) s_active[i] = active[i];
   const int version = tid == 0 ? *tbl_version + *mem_version : 0;
-  for (int i = tid; i < P * words; i += kMapThreads) s_bm[i] = 0u;
+  for (int i = tid; i < P * stride; i += kMapThreads) s_bm[i] = 0u;
   if (tid < 2) s_drop[tid] = 0;
   __syncthreads();
 
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
         } else {
           int sel = (policy == EEP_FIRST_LIVE || n == 1) ? 0 : t % n;
           p = s_live[s_off[e] + sel];
-          atomicOr(&s_bm[p * words + (t >> 5)], 1u << (t & 31));
+          atomicOr(&s_bm[p * stride + (t >> 5)], 1u << (t & 31));
         }
       }
     }
@@ -432,7 +433,7 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
 
   for (int p = tid; p < P; p += kMapThreads) {
     int c = 0;
-    for (int w = 0; w < words; ++w) c += __popc(s_bm[p * words + w]);
+    for (int w = 0; w < words; ++w) c += __popc(s_bm[p * stride + w]);
     s_count[p] = c;
   }
   // pairs per (source rank, slot): the tokens of a source rank are a bit range;
@@ -440,7 +441,7 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
   for (int b = tid >> 6; b < R; b += kMapThreads / 64)
     for (int p = tid & 63; p < P; p += 64)
       cnt_src[b * P + p] =
-          popc_range(&s_bm[p * words], b * tokens_per_rank, (b + 1) * tokens_per_rank);
+          popc_range(&s_bm[p * stride], b * tokens_per_rank, (b + 1) * tokens_per_rank);
   __syncthreads();
   block_exclusive_scan<kMapThreads>(s_count, s_offset, s_wave, P);
 
@@ -450,7 +451,7 @@ __global__ __launch_bounds__(kMapThreads) void k_layout_small(
     int row = -1;
     if (p >= 0) {
       int t = i / k;
-      const uint32_t* bm = &s_bm[p * words];
+      const uint32_t* bm = &s_bm[p * stride];
       int rank = __popc(bm[t >> 5] & ((1u << (t & 31)) - 1u));  // earlier tokens in this slot
       for (int w = 0; w < (t >> 5); ++w) rank += __popc(bm[w]);
       row = s_offset[p] + rank;

@@ -635,11 +635,13 @@ def test_one_context_many_batch_sizes_in_a_row(oracle):
 
 
 @pytest.mark.parametrize("policy", [binding.SPREAD, binding.FIRST_LIVE])
-@pytest.mark.parametrize("R,T,k,failed", [(32, 128, 8, (13,)), (32, 160, 8, (13,)), (4, 128, 2, ()),
+@pytest.mark.parametrize("R,T,k,failed", [(32, 128, 8, (13,)), (32, 160, 8, (13,)), (32, 192, 8, (31,)),
+                                          (32, 224, 8, (0,)), (4, 192, 2, (1,)), (4, 196, 2, ()),
+                                          (4, 128, 2, ()),
                                           (8, 40, 20, (2, 5)), (2, 128, 8, ()), (64, 128, 8, (0, 63)),
                                           (16, 32, 32, (7,)), (1, 128, 8, ())])
 def test_small_batches_around_the_single_workgroup_limit(oracle, policy, R, T, k, failed):
-    """Batches of at most 128 tokens and 1024 pairs are laid out by one workgroup in one
+    """Batches of at most 192 tokens and 1536 pairs are laid out by one workgroup in one
     launch; just above either limit the tiled path runs.  Both must give the oracle's
     layout: rank boundaries inside a bitmap word, k up to 32, failed first and last
     ranks, one rank only."""
