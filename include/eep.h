@@ -46,7 +46,8 @@ typedef enum {
   EEP_ERR_ALIGN = -2,       /* a row size or a base pointer is not 16-byte aligned   */
   EEP_ERR_COVERAGE = -3,    /* update would leave a logical expert with no live replica */
   EEP_ERR_HIP = -4,         /* a HIP runtime call failed; see eep_last_hip_error     */
-  EEP_ERR_STATE = -5        /* call order violated (e.g. dispatch before dispatch_layout) */
+  EEP_ERR_STATE = -5,       /* call order violated (e.g. dispatch before dispatch_layout) */
+  EEP_ERR_SCRATCH = -6      /* the batch needs more scratch than the fixed static array holds */
 } eep_status;
 
 typedef enum { EEP_F32 = 0, EEP_BF16 = 1, EEP_FP8_E4M3 = 2 } eep_dtype;
@@ -160,6 +161,47 @@ int eep_update_placement(eep_ctx* ctx, const int32_t* phys_to_logical_host, void
  * rows of one slot are contiguous and ordered by ascending token.
  * Results stay in the context (see eep_view). */
 int eep_dispatch_layout(eep_ctx* ctx, const int32_t* topk_idx, int32_t T, void* stream);
+
+/* eep_dispatch_layout for callers that cannot allocate device memory: code
+ * under hipGraph capture, tight serving loops, harnesses that forbid hipMalloc
+ * (and therefore eep_create).  Same kernels, same results, no context: the
+ * caller passes the tables and every output array as device pointers, and the
+ * pass's scratch (per-tile slot counts and prefixes, per-tile drop counters)
+ * lives in a static device array of EEP_NOALLOC_SCRATCH_BYTES inside the
+ * library; each GPU the library runs on holds that array until the process ends.
+ * The call makes no hipMalloc / hipFree and no allocating library call.
+ *   shape          R, S, E, k, eep_policy (host struct, read before returning)
+ *   topk_idx       device int32[T, k]
+ *   active         device int32[R]          (e.g. eep_view.active of a context)
+ *   l2p_off        device int32[E+1]        replica lists in canonical order, as
+ *   l2p_list       device int32[P]          eep_host_replica_lists writes them
+ *   table_version  device int32[1] copied to status[3], or NULL for 0
+ *   out            host struct of device pointers the caller owns:
+ *                  slot_of[T*k], row_of[T*k], src_of[T*k], count[P], offset[P+1],
+ *                  rank_count[R], rank_offset[R+1], cnt_src[R*P], status[4];
+ *                  same contents as the eep_view arrays after eep_dispatch_layout
+ * Limits: those of eep_create, and the batch's scratch must fit the array:
+ * eep_noalloc_scratch_needed(R, S, T) <= EEP_NOALLOC_SCRATCH_BYTES, otherwise
+ * EEP_ERR_SCRATCH and nothing is queued (512 + 8*tiles*(P+1) bytes rounded up,
+ * tiles = R * ceil(T/R / 128): 75 KB at T=4096, R=32, P=288).
+ * All calls on one GPU share the one array, which keeps the previous call's
+ * contents (no word needs clearing: each pass overwrites what it reads): calls
+ * whose kernels may overlap on one GPU -- different streams, or graphs launched
+ * concurrently -- race; keep them on one stream or order them with events. */
+#define EEP_NOALLOC_SCRATCH_BYTES (4 * 1024 * 1024)
+typedef struct {
+  int32_t num_ranks, slots_per_rank, num_logical, topk, policy;
+} eep_layout_shape;
+typedef struct {
+  int32_t *slot_of, *row_of, *src_of, *count, *offset, *rank_count, *rank_offset, *cnt_src,
+      *status;
+} eep_layout_out;
+int eep_dispatch_layout_noalloc(const eep_layout_shape* shape, const int32_t* topk_idx,
+                                const int32_t* active, const int32_t* l2p_off,
+                                const int32_t* l2p_list, const int32_t* table_version,
+                                const eep_layout_out* out, int32_t T, void* stream);
+/* Host only: scratch bytes a batch of T tokens needs (negative = eep_status). */
+int64_t eep_noalloc_scratch_needed(int32_t num_ranks, int32_t slots_per_rank, int32_t T);
 
 /* recv_x[row_of[t, j], :] = x[t, :] for every routed pair (Fig. 7, dispatch
  * path; inactive ranks are never written).  x: device [T, H] x_dtype;

@@ -11,7 +11,8 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libeep.so")
 
-OK, ERR_INVALID_ARG, ERR_ALIGN, ERR_COVERAGE, ERR_HIP, ERR_STATE = 0, -1, -2, -3, -4, -5
+OK, ERR_INVALID_ARG, ERR_ALIGN, ERR_COVERAGE, ERR_HIP, ERR_STATE, ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6
+NOALLOC_SCRATCH_BYTES = 4 * 1024 * 1024
 F32, BF16, FP8_E4M3 = 0, 1, 2
 SPREAD, FIRST_LIVE = 0, 1
 STUB_IDENTITY, STUB_SCALE, STUB_DEQUANT = 0, 1, 2
@@ -36,6 +37,19 @@ class _Config(ctypes.Structure):
 
 class _View(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in VIEW_FIELDS]
+
+
+class _LayoutShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("num_ranks", "slots_per_rank", "num_logical", "topk",
+                                              "policy")]
+
+
+LAYOUT_OUT_FIELDS = ["slot_of", "row_of", "src_of", "count", "offset", "rank_count", "rank_offset",
+                     "cnt_src", "status"]
+
+
+class _LayoutOut(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in LAYOUT_OUT_FIELDS]
 
 
 _lib = None
@@ -66,6 +80,8 @@ def load():
         "eep_set_membership": [vp, vp, vp],
         "eep_update_placement": [vp, vp, vp],
         "eep_dispatch_layout": [vp, vp, i32, vp],
+        "eep_dispatch_layout_noalloc": [ctypes.POINTER(_LayoutShape), vp, vp, vp, vp, vp,
+                                        ctypes.POINTER(_LayoutOut), i32, vp],
         "eep_dispatch": [vp, vp, vp, vp, vp, i32, vp],
         "eep_dispatch_quant": [vp, vp, vp, vp, i32, vp],
         "eep_combine": [vp, vp, vp, vp, i32, vp],
@@ -100,6 +116,8 @@ def load():
         fn = getattr(lib, name)
         fn.argtypes = argtypes
         fn.restype = ctypes.c_int
+    lib.eep_noalloc_scratch_needed.argtypes = [i32, i32, i32]
+    lib.eep_noalloc_scratch_needed.restype = i64
     lib.eep_strerror.argtypes = [ctypes.c_int]
     lib.eep_strerror.restype = ctypes.c_char_p
     _lib = lib
@@ -169,6 +187,26 @@ def host_tiling(T, R):
     _check(load().eep_host_tiling(T, R, out.ctypes.data), "eep_host_tiling")
     return dict(tokens_per_rank=int(out[0]), tiles_per_rank=int(out[1]), tile_tokens=int(out[2]),
                 num_tiles=int(out[3]))
+
+
+def noalloc_scratch_needed(R, S, T):
+    """Bytes of the static scratch array a batch of T tokens needs (host only)."""
+    n = load().eep_noalloc_scratch_needed(R, S, T)
+    if n < 0:
+        _check(int(n), "eep_noalloc_scratch_needed")
+    return int(n)
+
+
+def dispatch_layout_noalloc(*, R, S, E, k, policy, topk_idx, active, l2p_off, l2p_list, out, T,
+                            table_version=None, stream=None):
+    """eep_dispatch_layout_noalloc: tables and outputs are device tensors (or raw
+    addresses) the caller owns; `out` maps the names in LAYOUT_OUT_FIELDS to them."""
+    shape = _LayoutShape(R, S, E, k, policy)
+    o = _LayoutOut(*[_ptr(out[n]) for n in LAYOUT_OUT_FIELDS])
+    _check(load().eep_dispatch_layout_noalloc(ctypes.byref(shape), _ptr(topk_idx), _ptr(active),
+                                              _ptr(l2p_off), _ptr(l2p_list), _ptr(table_version),
+                                              ctypes.byref(o), T, _stream(stream)),
+           "eep_dispatch_layout_noalloc")
 
 
 SRC_NONE, SRC_LOCAL, SRC_PEER, SRC_DRAM = -1, 0, 1, 2

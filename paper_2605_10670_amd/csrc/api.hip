@@ -27,6 +27,7 @@ const char* eep_strerror(int code) {
     case EEP_ERR_COVERAGE: return "a logical expert would have no live replica";
     case EEP_ERR_HIP: return "HIP runtime error";
     case EEP_ERR_STATE: return "call order violated";
+    case EEP_ERR_SCRATCH: return "batch needs more scratch than the static array holds";
     default: return "unknown error";
   }
 }
@@ -92,8 +93,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   Tiling g = make_tiling(c->T_max - c->T_max % c->R, c->R);
   c->max_tiles = g.num_tiles > 0 ? g.num_tiles : 1;
   // the map kernel keeps its tables in LDS; refuse shapes that do not fit 64 KiB
-  size_t lds = map_lds_bytes(c->E, c->P, c->R, kTileTokens, c->k);
-  if (lds > 60 * 1024 || sizeof(int32_t) * ((size_t)3 * c->P + 1) > 60 * 1024) {
+  if (!layout_shape_fits(c->E, c->P, c->R, c->k)) {
     delete c;
     return EEP_ERR_INVALID_ARG;
   }

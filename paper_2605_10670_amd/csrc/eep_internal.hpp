@@ -17,6 +17,7 @@ constexpr int kBitmapWords = kTileTokens / 32;
 constexpr int kMaxTopk = 32;
 constexpr int kDedupMaxRanks = 1024;  // the de-duplicated layout keeps per-rank bitmaps in LDS
 constexpr int kPatchInts = 512;  // ints carried by value in one table-patch launch
+constexpr size_t kLayoutLdsLimit = 60 * 1024;  // the layout kernels keep their tables in LDS
 
 struct Tiling {
   int tokens_per_rank;  // T / R
@@ -111,6 +112,19 @@ int host_uncovered_experts(int P, int E, int S, const int32_t* p2l, const int32_
 void host_replica_lists(int P, int E, int S, int S_prim, const int32_t* p2l, int32_t* l2p_off,
                         int32_t* l2p_list);
 // layout.hip
+// Everything one layout pass touches, as plain device pointers: the context's
+// arrays for eep_dispatch_layout, the caller's arrays plus the static scratch
+// array for eep_dispatch_layout_noalloc.
+struct LayoutIO {
+  int R, S, P, E, k, policy;
+  const int32_t *topk_idx, *l2p_off, *l2p_list, *active, *tbl_version, *mem_version;
+  int32_t *slot_of, *row_of, *src_of, *count, *offset, *rank_count, *rank_offset, *cnt_src, *status;
+  // scratch: per-tile slot counts and prefixes [tiles][P], per-tile drop counters [tiles],
+  // the step counter
+  int32_t *cnt_tile, *base_tile, *blk_unc, *blk_msk, *step_epoch;
+};
+bool layout_shape_fits(int E, int P, int R, int k);  // tables fit the kernels' LDS budget
+hipError_t launch_layout(const LayoutIO& io, int T, hipStream_t st);
 hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st);
 // data.hip
 hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,

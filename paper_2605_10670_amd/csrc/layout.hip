@@ -769,64 +769,79 @@ hipError_t launch_dedup_layout(eep_ctx* c, int T, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st) {
-  Tiling g = make_tiling(T, c->R);
-  const bool k8 = c->k == 8;
+bool layout_shape_fits(int E, int P, int R, int k) {
+  return map_lds_bytes(E, P, R, kTileTokens, k) <= kLayoutLdsLimit &&
+         sizeof(int32_t) * ((size_t)3 * P + 1) <= kLayoutLdsLimit;
+}
+
+hipError_t launch_layout(const LayoutIO& c, int T, hipStream_t st) {
+  Tiling g = make_tiling(T, c.R);
+  const bool k8 = c.k == 8;
   if (g.num_tiles == 0) {
-    hipLaunchKernelGGL(k_empty_step, dim3(1), dim3(256), 0, st, c->tbl_version,
-                       c->mem->mem_version, c->count,
-                       c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
-                       c->step_epoch, c->R, c->P);
+    hipLaunchKernelGGL(k_empty_step, dim3(1), dim3(256), 0, st, c.tbl_version, c.mem_version,
+                       c.count, c.offset, c.rank_count, c.rank_offset, c.cnt_src, c.status,
+                       c.step_epoch, c.R, c.P);
     return hipGetLastError();
   }
-  if (T <= kSmallTokens && T * c->k <= kSmallPairs &&
-      small_lds_bytes(c->E, c->P, c->R, T, c->k) <= 60 * 1024) {
+  if (T <= kSmallTokens && T * c.k <= kSmallPairs &&
+      small_lds_bytes(c.E, c.P, c.R, T, c.k) <= kLayoutLdsLimit) {
     auto kern = k8 ? k_layout_small<8> : k_layout_small<0>;
-    hipLaunchKernelGGL(kern, dim3(1), dim3(kMapThreads), small_lds_bytes(c->E, c->P, c->R, T, c->k),
-                       st, topk_idx, c->l2p_off, c->l2p_list, c->active, c->tbl_version,
-                       c->mem->mem_version, c->slot_of, c->row_of, c->src_of, c->count, c->offset,
-                       c->rank_count, c->rank_offset, c->cnt_src, c->status, c->step_epoch, c->k,
-                       c->E, c->R, c->S, c->P, T, g.tokens_per_rank, c->cfg.policy);
+    hipLaunchKernelGGL(kern, dim3(1), dim3(kMapThreads), small_lds_bytes(c.E, c.P, c.R, T, c.k),
+                       st, c.topk_idx, c.l2p_off, c.l2p_list, c.active, c.tbl_version,
+                       c.mem_version, c.slot_of, c.row_of, c.src_of, c.count, c.offset,
+                       c.rank_count, c.rank_offset, c.cnt_src, c.status, c.step_epoch, c.k, c.E,
+                       c.R, c.S, c.P, T, g.tokens_per_rank, c.policy);
     return hipGetLastError();
   }
   {
-    size_t lds = map_lds_bytes(c->E, c->P, c->R, g.tile_tokens, c->k);
+    size_t lds = map_lds_bytes(c.E, c.P, c.R, g.tile_tokens, c.k);
     auto kern = k8 ? k_map_count<8> : k_map_count<0>;
-    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kMapThreads), lds, st, topk_idx, c->l2p_off,
-                       c->l2p_list, c->active, c->slot_of, c->row_of, c->cnt_tile, c->blk_unc,
-                       c->blk_msk, c->k, c->E, c->R, c->S, c->P, g.tokens_per_rank,
-                       g.tiles_per_rank, g.tile_tokens, c->cfg.policy);
+    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kMapThreads), lds, st, c.topk_idx, c.l2p_off,
+                       c.l2p_list, c.active, c.slot_of, c.row_of, c.cnt_tile, c.blk_unc, c.blk_msk,
+                       c.k, c.E, c.R, c.S, c.P, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens,
+                       c.policy);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  const bool fused = g.num_tiles <= 64 && g.tile_tokens * c->k <= kFusedThreads * kFusedPairs;
+  const bool fused = g.num_tiles <= 64 && g.tile_tokens * c.k <= kFusedThreads * kFusedPairs;
   if (fused) {
-    size_t lds = sizeof(int32_t) * ((size_t)3 * c->P + 1);
+    size_t lds = sizeof(int32_t) * ((size_t)3 * c.P + 1);
     auto kern = k8 ? k_scan_position<8> : k_scan_position<0>;
-    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kFusedThreads), lds, st, c->cnt_tile,
-                       c->blk_unc, c->blk_msk, c->tbl_version, c->mem->mem_version, c->slot_of, c->row_of,
-                       c->src_of,
-                       c->count, c->offset, c->rank_count, c->rank_offset, c->cnt_src, c->status,
-                       c->step_epoch, c->k, g.num_tiles, g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, c->R,
-                       c->S, c->P);
+    hipLaunchKernelGGL(kern, dim3(g.num_tiles), dim3(kFusedThreads), lds, st, c.cnt_tile,
+                       c.blk_unc, c.blk_msk, c.tbl_version, c.mem_version, c.slot_of, c.row_of,
+                       c.src_of, c.count, c.offset, c.rank_count, c.rank_offset, c.cnt_src,
+                       c.status, c.step_epoch, c.k, g.num_tiles, g.tokens_per_rank,
+                       g.tiles_per_rank, g.tile_tokens, c.R, c.S, c.P);
     return hipGetLastError();
   }
   int tiles_per_wave = (g.num_tiles + kPrefixWaves - 1) / kPrefixWaves;
-  hipLaunchKernelGGL(k_tile_prefix, dim3((c->P + 63) / 64), dim3(kPrefixThreads), 0, st,
-                     c->cnt_tile, c->base_tile, c->count, g.num_tiles, tiles_per_wave, c->P);
+  hipLaunchKernelGGL(k_tile_prefix, dim3((c.P + 63) / 64), dim3(kPrefixThreads), 0, st, c.cnt_tile,
+                     c.base_tile, c.count, g.num_tiles, tiles_per_wave, c.P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  int total_pairs = T * c->k;
-  size_t lds_pos = sizeof(int32_t) * ((size_t)2 * c->P + 1);
+  int total_pairs = T * c.k;
+  size_t lds_pos = sizeof(int32_t) * ((size_t)2 * c.P + 1);
   auto kern = k8 ? k_position<8> : k_position<0>;
   hipLaunchKernelGGL(kern, dim3((total_pairs + kPosThreads - 1) / kPosThreads), dim3(kPosThreads),
-                     lds_pos, st, c->slot_of, c->base_tile, c->count, c->blk_unc, c->blk_msk,
-                     c->tbl_version, c->mem->mem_version, c->row_of, c->src_of, c->cnt_src, c->offset,
-                     c->rank_count,
-                     c->rank_offset, c->status, c->step_epoch, c->k,
-                     g.tokens_per_rank, g.tiles_per_rank, g.tile_tokens, g.num_tiles, total_pairs,
-                     c->R, c->S, c->P);
+                     lds_pos, st, c.slot_of, c.base_tile, c.count, c.blk_unc, c.blk_msk,
+                     c.tbl_version, c.mem_version, c.row_of, c.src_of, c.cnt_src, c.offset,
+                     c.rank_count, c.rank_offset, c.status, c.step_epoch, c.k, g.tokens_per_rank,
+                     g.tiles_per_rank, g.tile_tokens, g.num_tiles, total_pairs, c.R, c.S, c.P);
   return hipGetLastError();
+}
+
+hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st) {
+  LayoutIO io;
+  io.R = c->R; io.S = c->S; io.P = c->P; io.E = c->E; io.k = c->k; io.policy = c->cfg.policy;
+  io.topk_idx = topk_idx;
+  io.l2p_off = c->l2p_off; io.l2p_list = c->l2p_list; io.active = c->active;
+  io.tbl_version = c->tbl_version; io.mem_version = c->mem->mem_version;
+  io.slot_of = c->slot_of; io.row_of = c->row_of; io.src_of = c->src_of;
+  io.count = c->count; io.offset = c->offset; io.rank_count = c->rank_count;
+  io.rank_offset = c->rank_offset; io.cnt_src = c->cnt_src; io.status = c->status;
+  io.cnt_tile = c->cnt_tile; io.base_tile = c->base_tile; io.blk_unc = c->blk_unc;
+  io.blk_msk = c->blk_msk; io.step_epoch = c->step_epoch;
+  return launch_layout(io, T, st);
 }
 
 }  // namespace eep

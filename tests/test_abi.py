@@ -58,3 +58,17 @@ def test_workspace_size_is_host_only_and_checks_the_config():
     with pytest.raises(binding.EepError) as ei:
         binding.workspace_bytes(**dict(shape, hidden=7))               # 14-byte rows
     assert ei.value.code == binding.ERR_ALIGN
+
+
+def test_noalloc_scratch_size_is_host_only():
+    from paper_2605_10670_amd import binding
+    # decode shape: 32 tiles x 288 slots, two int matrices + two per-tile counters + header
+    assert binding.noalloc_scratch_needed(32, 9, 4096) == 512 + 2 * 32 * 288 * 4 + 2 * 64 * 4
+    assert binding.noalloc_scratch_needed(32, 9, 0) == 512
+    assert binding.noalloc_scratch_needed(32, 9, 16384) < binding.NOALLOC_SCRATCH_BYTES
+    assert binding.noalloc_scratch_needed(32, 9, 32 * 128 * 2048) > binding.NOALLOC_SCRATCH_BYTES
+    with pytest.raises(binding.EepError):
+        binding.noalloc_scratch_needed(32, 9, 33)
+    # the header's constant and the binding's agree
+    text = open(os.path.join(ROOT, "include", "eep.h")).read()
+    assert "#define EEP_NOALLOC_SCRATCH_BYTES (4 * 1024 * 1024)" in text
