@@ -90,9 +90,14 @@ typedef struct {
 
 typedef struct eep_ctx eep_ctx;
 
-/* Allocates the device tables and layout arrays on the current device
- * (hipMalloc; sizes depend only on the config) and initialises them to
- * "all ranks live, all slots empty".  Synchronises the device once.
+/* Creates one EP instance's routing state: the GPU-resident table of the
+ * instance's ranks (Sec. 4.1; here its `active` column), the expert-location
+ * metadata (Sec. 5.1) and the per-step layout arrays, all at device addresses
+ * that stay fixed until eep_destroy -- the stable pointers a captured graph
+ * holds (Sec. 2.3; Fig. 4, Fig. 8).
+ * Allocates them on the current device (hipMalloc; sizes depend only on the
+ * config) and initialises them to "all ranks live, all slots empty".
+ * Synchronises the device once.
  * Row sizes (H * sizeof(dtype)) must be multiples of 16 bytes (EEP_ERR_ALIGN).
  * On error *out is NULL. */
 int eep_create(const eep_config* cfg, eep_ctx** out);
@@ -122,7 +127,9 @@ int eep_create_with_workspace(const eep_config* cfg, void* workspace, int64_t wo
  * destroyed before the context that eep_create made. */
 int eep_create_attached(const eep_config* cfg, eep_ctx* parent, eep_ctx** out);
 
-/* Waits for the device, frees everything the context owns.  NULL is OK.
+/* Ends the lifetime of the stable pointers (Fig. 4, Fig. 8): graphs captured
+ * with this context must not be replayed afterwards.  Waits for the device,
+ * frees everything the context owns.  NULL is OK.
  * EEP_ERR_STATE if attached contexts of this instance still exist. */
 int eep_destroy(eep_ctx* ctx);
 
@@ -138,7 +145,18 @@ int eep_destroy(eep_ctx* ctx);
  *
  * To stay valid at every step boundary follow the paper's order (Fig. 6):
  *   failure: eep_update_placement(repaired), then eep_set_membership(dead);
- *   rejoin:  eep_set_membership(live), then eep_update_placement(preferred). */
+ *   rejoin:  eep_set_membership(live), then eep_update_placement(preferred).
+ *
+ * With GPU-side failure detection on (eep_set_detection), a waiting kernel may
+ * have dropped a rank that the host has not heard of yet (Sec. 4.1: the report
+ * reaches the host only after the kernel has exited).  From the moment an
+ * eep_combine with detection on is queued (or a graph holding one is launched)
+ * until eep_read_failures has been called, the host's copy of the mask counts
+ * as out of date: eep_set_membership returns EEP_ERR_STATE (it would rewrite the
+ * whole mask and could bring a dropped rank back), and so do
+ * eep_update_placement and eep_apply_repair of a context with strict_coverage
+ * (their coverage check needs the current mask).  Nothing is changed then;
+ * call eep_read_failures and repeat the call. */
 
 /* active_host: host int32[R]; 0 = failed (receives nothing), non-zero = live.
  * This is the `active` column of the peer table (Fig. 7). */
@@ -151,7 +169,14 @@ int eep_update_placement(eep_ctx* ctx, const int32_t* phys_to_logical_host, void
 
 /* ---- per-step calls: graph-capturable, grids depend only on T ----------- */
 
-/* Routing + layout of one step.  topk_idx: device int32[T, k], the router's
+/* Routing + layout of one step: the table lookups of the dispatch path
+ * (Fig. 7: every transfer consults the destination's entry and skips it when
+ * `active` is 0; Sec. 5.1: slot -> logical expert and all locations of a
+ * logical expert) and the placement of the payload rows into contiguous
+ * per-expert receive buffers (Sec. 4.1 refers to prior work for it).  The
+ * result satisfies the validity contract of Sec. 3.2: rows go to active ranks
+ * only, and to a slot that holds the pair's logical expert.
+ * topk_idx: device int32[T, k], the router's
  * logical expert per (token, j).  T must satisfy 0 <= T <= T_max, T % R == 0
  * (tokens [b*T/R, (b+1)*T/R) belong to source rank b).
  * For every pair it picks the live replica slot (slot_of, or -1 when the
@@ -241,8 +266,8 @@ int eep_combine(eep_ctx* ctx, const void* y, const float* topk_w, void* out, int
 int eep_expert_stub(eep_ctx* ctx, int32_t kind, const void* recv_x, const float* recv_scale,
                     const float* expert_scale, void* y, int32_t T, void* stream);
 
-/* ---- GPU-side failure detection (Sec. 3.4; Sec. 4.1 "Failure detection from
- * the GPU side"; Fig. 7: "timeout -> set e.active = 0 and continue") ----------
+/* ---- GPU-side failure detection (Sec. 3.4; Sec. 4.1, the paragraph on
+ * failure detection from the GPU side; the time-out remark in Fig. 7's listing)
  * One-GPU emulation of the paper's signal counters.  Every eep_dispatch_layout
  * advances a device-side step epoch.  The expert stage announces "the outputs of
  * rank r for this step are there" by storing the epoch into rank r's signal word
@@ -267,16 +292,21 @@ int eep_signal_experts_done(eep_ctx* ctx, void* stream);
 /* Test knob: withhold_host[R], non-zero = that rank never signals (a silent
  * peer).  This is how a failure is injected on one GPU. */
 int eep_debug_withhold_signal(eep_ctx* ctx, const int32_t* withhold_host, void* stream);
-/* Waits for `stream`, copies the failure report to failed_host[R] (1 = dropped
- * by a kernel since the last call), folds it into the host's copy of the active
- * mask and clears the report. */
+/* Waits for `stream` (for the whole device when the instance has attached
+ * contexts, whose steps may run on other streams), copies the failure report of
+ * every context of the instance to failed_host[R] (1 = dropped by a kernel since
+ * the last call), folds it into the host's copy of the active mask and clears
+ * the report.  Afterwards the table updates are accepted again (see above). */
 int eep_read_failures(eep_ctx* ctx, int32_t* failed_host, void* stream);
 
 /* ---- introspection ------------------------------------------------------ */
 
-/* Device addresses of the context's arrays (all int32, stable for the
- * context's lifetime; contents valid once the producing call has finished on
- * its stream).
+/* Device addresses of the context's arrays: the graph-visible state of
+ * Sec. 3.2 (condition 3) and Fig. 4 / Fig. 8 -- fixed pointers, mutable
+ * contents -- for callers whose own kernels read the routing results (expert
+ * kernels need offset/count; Sec. 5.1's metadata is phys_to_logical + l2p_*).
+ * All int32, stable for the context's lifetime; contents valid once the
+ * producing call has finished on its stream.
  *   active[R], phys_to_logical[P], l2p_off[E+1], l2p_list[P]  tables
  *   slot_of[T,k], row_of[T,k]      per pair; -1 when not routed
  *   src_of[T*k]                    row -> t*k+j; -1 for rows >= N
@@ -285,7 +315,8 @@ int eep_read_failures(eep_ctx* ctx, int32_t* failed_host, void* stream);
  *   cnt_src[R,P]                   pairs per (source rank, slot)
  *   status[4]                      {N, n_uncovered, n_masked, table version}
  *                                  (version = placement updates of this context
- *                                  + membership updates of the instance) */
+ *                                  + membership changes of the instance: host
+ *                                  updates and drops made by waiting kernels) */
 typedef struct {
   const int32_t *active, *phys_to_logical, *l2p_off, *l2p_list;
   const int32_t *slot_of, *row_of, *src_of;
@@ -379,10 +410,10 @@ int eep_plan_transition(int32_t R, int32_t S, int32_t S_prim, int32_t E,
                         int32_t summary[4]);
 
 /* Carry out a planned repair (Sec. 3.5: local reuse / batched GPU-to-GPU
- * relocation / reload from the DRAM backup; Sec. 5.1: "moves weights to match
- * that placement", the active mask being looked up when each transfer is
- * issued), then publish the placement (as eep_update_placement does), all in
- * stream order.
+ * relocation / reload from the DRAM backup; Sec. 5.1: the weights are moved to
+ * where the new placement wants them, the active mask being looked up when
+ * each transfer is issued), then publish the placement (as
+ * eep_update_placement does), all in stream order.
  *   weights  device memory, [P][slot_bytes]: the expert weight store, slot-major
  *            (rank r owns slots [r*S, (r+1)*S)); updated in place.
  *   backup   [E][slot_bytes], readable by the GPU: device memory, or host memory

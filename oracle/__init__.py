@@ -171,6 +171,20 @@ def combine_chain32(y, y_dtype, w, row_of):
     return out
 
 
+def detect_round(slot_of, row_of, active, arrived, S):
+    """One combine-side wait for the signals of the active ranks (Sec. 3.4, Sec. 4.1).
+    -> dict(active, report, row_of, withdrawn): the mask later steps see, the failure
+    report the host reads after the step, the rows the combine of THIS step uses."""
+    slot_of, rows = _i32(slot_of), _i32(row_of).copy()
+    act, arr = _i32(active).copy(), _i32(arrived)
+    T, k = slot_of.shape
+    report = np.zeros(act.size, np.int32)
+    fn = lib().eeo_detect_round
+    fn.restype = ctypes.c_int64
+    n = fn(T, k, act.size, S, _p(slot_of), _p(arr), _p(act), _p(report), _p(rows))
+    return dict(active=act, report=report, row_of=rows, withdrawn=int(n))
+
+
 def bf16_to_f32(bits):
     bits = np.ascontiguousarray(bits, np.uint16)
     out = np.empty(bits.shape, np.float32)

@@ -24,6 +24,8 @@
  *               batches would see).
  *   combine     Sec. 4.1: reduce the expert outputs per token, weighted by the
  *               router weights (Sec. 2.1).
+ *   detection   Sec. 3.4 and Sec. 4.1: a peer whose signal does not arrive
+ *               within the time-out is dropped by the waiting kernel.
  *
  * Readings where the paper is silent:
  *   - canonical replica order: primary slots first, then ascending slot id;
@@ -348,6 +350,40 @@ void eeo_stub_dequant(int N, int H, int group, const uint8_t* q, const float* sc
       float sc = scale[(int64_t)row * G + h / group];
       y[(int64_t)row * H + h] = eeo_f32_to_bf16((float)((double)v * (double)sc));
     }
+}
+
+/* ---------- failure detection from the GPU side (Sec. 3.4; Sec. 4.1, the
+ * paragraph on per-rank signal counters; the time-out remark in Fig. 7) --------
+ * One round of waiting, seen from the combine side of a step whose routing
+ * (slot_of, row_of) was made under the mask active[R]:
+ *   arrived[r] != 0  rank r's signal for this round came within the time-out.
+ * Only ACTIVE peers are awaited.  An active rank whose signal did not arrive is
+ * deemed failed: its active entry is cleared (later steps route around it), it
+ * is put on the failure report that the host reads after the step, and the
+ * pairs routed to it in this step contribute nothing (their requests are
+ * failed, Sec. 3.1): their row_of entry becomes -1 so that the combine skips
+ * them.  Arrays are updated in place; report[R] is written (1 = dropped now).
+ * Returns the number of pairs withdrawn. */
+int64_t eeo_detect_round(int T, int k, int R, int S, const int32_t* slot_of,
+                         const int32_t* arrived, int32_t* active, int32_t* report,
+                         int32_t* row_of) {
+  for (int r = 0; r < R; ++r) {
+    report[r] = 0;
+    if (active[r] == 0) continue; /* not awaited */
+    if (arrived[r] != 0) continue;
+    active[r] = 0;
+    report[r] = 1;
+  }
+  int64_t withdrawn = 0;
+  for (int i = 0; i < T * k; ++i) {
+    int p = slot_of[i];
+    if (p < 0 || row_of[i] < 0) continue;
+    if (report[p / S]) {
+      row_of[i] = -1;
+      ++withdrawn;
+    }
+  }
+  return withdrawn;
 }
 
 /* ---------- O8: combine ------------------------------------------------------

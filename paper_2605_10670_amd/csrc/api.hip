@@ -81,7 +81,6 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   c->y_row_bytes = (int64_t)c->H * dtype_bytes(f.y_dtype);
   c->out_row_bytes = (int64_t)c->H * dtype_bytes(f.out_dtype);
   c->scale_row_bytes = f.x_dtype == EEP_FP8_E4M3 ? (int64_t)(c->H / f.scale_group) * 4 : 0;
-  c->version = 0;
   c->layout_T = -1;
   c->last_hip_error = 0;
   c->slab = nullptr;
@@ -196,7 +195,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
     c->mem->active = c->own_active;
     c->mem->mem_version = c->mem_version_word;
     c->mem->h_active.assign(c->R, 1);
-    c->mem->version = 0;
+    c->mem->unread_round = false;
   }
   c->active = c->mem->active;
   // initial state: every slot empty, nothing laid out
@@ -272,6 +271,9 @@ int eep_destroy(eep_ctx* ctx) {
 int eep_set_membership(eep_ctx* c, const int32_t* active_host, void* stream) {
   if (!c || !active_host) return EEP_ERR_INVALID_ARG;
   eep_membership* m = c->mem;
+  // A waiting kernel may have dropped a rank that the host's copy of the mask still shows
+  // as live; rewriting the whole mask from the caller's array would bring it back.
+  if (m->unread_round) return EEP_ERR_STATE;
   std::vector<int32_t> a(c->R);
   for (int r = 0; r < c->R; ++r) a[r] = active_host[r] != 0 ? 1 : 0;
   // the mask is shared: every context of the instance that asked for strict
@@ -280,31 +282,45 @@ int eep_set_membership(eep_ctx* c, const int32_t* active_host, void* stream) {
     if (o->cfg.strict_coverage &&
         host_uncovered_experts(o->P, o->E, o->S, o->h_p2l.data(), a.data()) > 0)
       return EEP_ERR_COVERAGE;
-  hipError_t e = launch_patch(m->active, a.data(), c->R, m->mem_version, m->version + 1,
-                              (hipStream_t)stream);
+  hipError_t e = launch_patch(m->active, a.data(), c->R, m->mem_version, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e);
   m->h_active = a;
-  m->version += 1;
   return EEP_OK;
 }
 
-int eep_update_placement(eep_ctx* c, const int32_t* p2l_host, void* stream) {
-  if (!c || !p2l_host) return EEP_ERR_INVALID_ARG;
+}  // extern "C"
+
+namespace eep {
+
+// Checks and publishes a placement.  `mask_may_be_stale`: the caller has dealt with an
+// unread detection round itself (eep_apply_repair looks the device mask up per transfer).
+int publish_placement(eep_ctx* c, const int32_t* p2l_host, bool mask_may_be_stale,
+                      hipStream_t st) {
   for (int p = 0; p < c->P; ++p)
     if (p2l_host[p] < -1 || p2l_host[p] >= c->E) return EEP_ERR_INVALID_ARG;
-  if (c->cfg.strict_coverage && host_uncovered_experts(c->P, c->E, c->S, p2l_host, c->mem->h_active.data()) > 0)
-    return EEP_ERR_COVERAGE;
+  if (c->cfg.strict_coverage) {
+    // coverage is judged against the host's copy of the mask, which must be current
+    if (c->mem->unread_round && !mask_may_be_stale) return EEP_ERR_STATE;
+    if (host_uncovered_experts(c->P, c->E, c->S, p2l_host, c->mem->h_active.data()) > 0)
+      return EEP_ERR_COVERAGE;
+  }
   std::vector<int32_t> off(c->E + 1), list(c->P);
   host_replica_lists(c->P, c->E, c->S, c->S_prim, p2l_host, off.data(), list.data());
-  hipStream_t st = (hipStream_t)stream;
-  hipError_t e = launch_patch(c->p2l, p2l_host, c->P, nullptr, 0, st);
-  if (e == hipSuccess) e = launch_patch(c->l2p_off, off.data(), c->E + 1, nullptr, 0, st);
-  if (e == hipSuccess)
-    e = launch_patch(c->l2p_list, list.data(), c->P, c->tbl_version, c->version + 1, st);
+  hipError_t e = launch_patch(c->p2l, p2l_host, c->P, nullptr, st);
+  if (e == hipSuccess) e = launch_patch(c->l2p_off, off.data(), c->E + 1, nullptr, st);
+  if (e == hipSuccess) e = launch_patch(c->l2p_list, list.data(), c->P, c->tbl_version, st);
   if (e != hipSuccess) return fail_hip(c, e);
   c->h_p2l.assign(p2l_host, p2l_host + c->P);
-  c->version += 1;
   return EEP_OK;
+}
+
+}  // namespace eep
+
+extern "C" {
+
+int eep_update_placement(eep_ctx* c, const int32_t* p2l_host, void* stream) {
+  if (!c || !p2l_host) return EEP_ERR_INVALID_ARG;
+  return publish_placement(c, p2l_host, false, (hipStream_t)stream);
 }
 
 int eep_dispatch_layout(eep_ctx* c, const int32_t* topk_idx, int32_t T, void* stream) {
@@ -313,6 +329,7 @@ int eep_dispatch_layout(eep_ctx* c, const int32_t* topk_idx, int32_t T, void* st
   hipError_t e = launch_layout(c, topk_idx, T, (hipStream_t)stream);
   if (e != hipSuccess) return fail_hip(c, e);
   c->layout_T = T;
+  c->dedup_T = -1;  // the de-duplicated tables belong to the previous layout
   return EEP_OK;
 }
 
@@ -355,7 +372,10 @@ int eep_combine(eep_ctx* c, const void* y, const float* topk_w, void* out, int32
   if (!y || !topk_w || !out) return EEP_ERR_INVALID_ARG;
   if (!aligned16(y) || !aligned16(out)) return EEP_ERR_ALIGN;
   hipError_t e = hipSuccess;
-  if (c->detect_timeout_ticks > 0) e = launch_await(c, T, (hipStream_t)stream);
+  if (c->detect_timeout_ticks > 0) {
+    e = launch_await(c, T, (hipStream_t)stream);
+    c->mem->unread_round = true;  // until eep_read_failures has looked at the report
+  }
   if (e == hipSuccess) e = launch_combine(c, y, topk_w, out, T, (hipStream_t)stream);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
@@ -415,29 +435,36 @@ int eep_debug_withhold_signal(eep_ctx* c, const int32_t* withhold_host, void* st
   if (!c || !withhold_host) return EEP_ERR_INVALID_ARG;
   std::vector<int32_t> w(c->R);
   for (int r = 0; r < c->R; ++r) w[r] = withhold_host[r] != 0;
-  hipError_t e = launch_patch(c->withhold, w.data(), c->R, nullptr, 0, (hipStream_t)stream);
+  hipError_t e = launch_patch(c->withhold, w.data(), c->R, nullptr, (hipStream_t)stream);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
 
 int eep_read_failures(eep_ctx* c, int32_t* failed_host, void* stream) {
   if (!c || !failed_host) return EEP_ERR_INVALID_ARG;
+  eep_membership* m = c->mem;
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = hipStreamSynchronize(st);
-  if (e == hipSuccess)
-    e = hipMemcpy(failed_host, c->report, sizeof(int32_t) * c->R, hipMemcpyDeviceToHost);
+  // the mask is shared by every context of the instance, so every context's report counts;
+  // their steps may run on other streams
+  hipError_t e = m->members.size() > 1 ? hipDeviceSynchronize() : hipStreamSynchronize(st);
   if (e != hipSuccess) return fail_hip(c, e);
-  bool any = false;
-  for (int r = 0; r < c->R; ++r) {
-    failed_host[r] = failed_host[r] != 0;
-    if (failed_host[r]) {
-      c->mem->h_active[r] = 0;  // the kernel already cleared the device copy
-      any = true;
+  for (int r = 0; r < c->R; ++r) failed_host[r] = 0;
+  std::vector<int32_t> rep(c->R);
+  for (eep_ctx* o : m->members) {
+    e = hipMemcpy(rep.data(), o->report, sizeof(int32_t) * c->R, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(c, e);
+    bool any = false;
+    for (int r = 0; r < c->R; ++r)
+      if (rep[r] != 0) {
+        failed_host[r] = 1;
+        m->h_active[r] = 0;  // the kernel already cleared the device copy
+        any = true;
+      }
+    if (any) {
+      e = launch_fill(o->report, 0, c->R, st);
+      if (e != hipSuccess) return fail_hip(c, e);
     }
   }
-  if (any) {
-    e = launch_fill(c->report, 0, c->R, st);
-    if (e != hipSuccess) return fail_hip(c, e);
-  }
+  m->unread_round = false;
   return EEP_OK;
 }
 

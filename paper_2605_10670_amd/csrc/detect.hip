@@ -1,6 +1,6 @@
-// GPU-side failure detection, emulated on one GPU (paper Sec. 3.4 and Sec. 4.1
-// "Failure detection from the GPU side", Fig. 7 comment "timeout -> set
-// e.active = 0 and continue").
+// GPU-side failure detection, emulated on one GPU (paper Sec. 3.4; Sec. 4.1,
+// the paragraph on failure detection from the GPU side; the time-out remark in
+// the listing of Fig. 7).
 //
 // In the paper a sender bumps the receiver's signal counter after its payload
 // (RDMA atomic, or a release store over NVLink); the receiver polls its counter
@@ -34,6 +34,7 @@ __global__ __launch_bounds__(256) void k_signal(const int32_t* __restrict__ acti
 }
 
 __global__ __launch_bounds__(1024) void k_await(int32_t* __restrict__ active,
+                                                int32_t* __restrict__ mem_version,
                                                 const int32_t* __restrict__ signal,
                                                 const int32_t* __restrict__ step_epoch,
                                                 int32_t* __restrict__ report,
@@ -70,6 +71,7 @@ __global__ __launch_bounds__(1024) void k_await(int32_t* __restrict__ active,
   }
   __syncthreads();
   if (s_any == 0) return;
+  if (tid == 0) *mem_version = *mem_version + 1;  // the membership changed: status[3] shows it
   // rare path: pairs routed to a dropped rank contribute nothing to this step
   for (int i = tid; i < total_pairs; i += blockDim.x) {
     int p = slot_of[i];
@@ -85,7 +87,7 @@ hipError_t launch_signal(eep_ctx* c, hipStream_t st) {
 
 hipError_t launch_await(eep_ctx* c, int T, hipStream_t st) {
   hipLaunchKernelGGL(k_await, dim3(1), dim3(1024), sizeof(int32_t) * c->R, st, c->active,
-                     c->signal, c->step_epoch, c->report, c->slot_of, c->row_of, c->R, c->S,
+                     c->mem->mem_version, c->signal, c->step_epoch, c->report, c->slot_of, c->row_of, c->R, c->S,
                      T * c->k, (long long)c->detect_timeout_ticks,
                      (long long)c->detect_timeout_ticks * 8 + 1024);
   return hipGetLastError();

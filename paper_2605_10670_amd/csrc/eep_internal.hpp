@@ -57,9 +57,11 @@ struct PatchChunk {
 struct eep_membership {
   int R;
   int32_t* active;       // device [R]
-  int32_t* mem_version;  // device word: number of membership updates
+  int32_t* mem_version;  // device word: membership changes (host updates + ranks dropped by kernels)
   std::vector<int32_t> h_active;
-  int32_t version;
+  // A combine with failure detection has been queued since the last eep_read_failures: a
+  // kernel may have cleared bits of `active` that h_active still shows as set.
+  bool unread_round;
   std::vector<eep_ctx*> members;  // root first
 };
 
@@ -99,7 +101,6 @@ struct eep_ctx {
 
   // host shadows of the tables (coverage is validated without touching the GPU)
   std::vector<int32_t> h_p2l;
-  int32_t version;  // placement updates of this context
   int layout_T;  // T of the last dispatch_layout, -1 if none yet
   int last_hip_error;
   int64_t field_ints[EEP_V_NUM_FIELDS];
@@ -143,9 +144,11 @@ hipError_t launch_stub(eep_ctx* c, int kind, const void* recv_x, const float* re
 // detect.hip
 hipError_t launch_signal(eep_ctx* c, hipStream_t st);
 hipError_t launch_await(eep_ctx* c, int T, hipStream_t st);
+// api.hip
+int publish_placement(eep_ctx* c, const int32_t* p2l_host, bool mask_may_be_stale, hipStream_t st);
 // tables.hip
 hipError_t launch_patch(int32_t* dst, const int32_t* src_host, int n, int32_t* version_dst,
-                        int32_t version, hipStream_t st);
+                        hipStream_t st);
 hipError_t launch_fill(int32_t* dst, int32_t value, int64_t n, hipStream_t st);
 
 }  // namespace eep

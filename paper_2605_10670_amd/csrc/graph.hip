@@ -11,6 +11,9 @@ struct eep_graph {
   hipGraph_t graph;
   hipGraphExec_t exec;
   int64_t instantiations, exec_updates, launches;
+  // the instance whose contexts were captured with failure detection on (else null):
+  // every replay then holds a waiting kernel that may drop a rank
+  eep_membership* awaits;
 };
 
 extern "C" {
@@ -41,6 +44,9 @@ int eep_graph_end(eep_ctx* c, void* stream, eep_graph** out) {
     return EEP_ERR_HIP;
   }
   g->instantiations = 1;
+  g->awaits = nullptr;
+  for (eep_ctx* o : c->mem->members)
+    if (o->detect_timeout_ticks > 0) g->awaits = c->mem;
   *out = g;
   return EEP_OK;
 }
@@ -49,6 +55,7 @@ int eep_graph_launch(eep_graph* g, void* stream) {
   if (!g || !g->exec) return EEP_ERR_INVALID_ARG;
   hipError_t e = hipGraphLaunch(g->exec, (hipStream_t)stream);
   if (e != hipSuccess) return EEP_ERR_HIP;
+  if (g->awaits) g->awaits->unread_round = true;
   g->launches += 1;
   return EEP_OK;
 }

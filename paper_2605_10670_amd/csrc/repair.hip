@@ -119,9 +119,14 @@ int eep_apply_repair(eep_ctx* c, void* weights, const void* backup, int64_t slot
         return EEP_ERR_INVALID_ARG;
     }
   }
-  if (c->cfg.strict_coverage &&
-      host_uncovered_experts(P, c->E, S, new_p2l, c->mem->h_active.data()) > 0)
-    return EEP_ERR_COVERAGE;
+  // Sources are looked up in the device mask per transfer, so an unread detection round
+  // does not matter for the movement; the coverage check of a strict context does need a
+  // current mask.
+  if (c->cfg.strict_coverage) {
+    if (c->mem->unread_round) return EEP_ERR_STATE;
+    if (host_uncovered_experts(P, c->E, S, new_p2l, c->mem->h_active.data()) > 0)
+      return EEP_ERR_COVERAGE;
+  }
   const int n_moves = (int)dst.size();
   const int64_t slot_vecs = slot_bytes / 16;
   const int64_t chunks = (slot_vecs + kChunkVecs - 1) / kChunkVecs;
@@ -139,9 +144,9 @@ int eep_apply_repair(eep_ctx* c, void* weights, const void* backup, int64_t slot
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_fill(c->mv_outcome, EEP_REPAIR_UNTOUCHED, P, st);
   if (e == hipSuccess && n_moves > 0) {
-    e = launch_patch(c->mv_dst, dst.data(), n_moves, nullptr, 0, st);
-    if (e == hipSuccess) e = launch_patch(c->mv_src, src.data(), n_moves, nullptr, 0, st);
-    if (e == hipSuccess) e = launch_patch(c->mv_expert, expert.data(), n_moves, nullptr, 0, st);
+    e = launch_patch(c->mv_dst, dst.data(), n_moves, nullptr, st);
+    if (e == hipSuccess) e = launch_patch(c->mv_src, src.data(), n_moves, nullptr, st);
+    if (e == hipSuccess) e = launch_patch(c->mv_expert, expert.data(), n_moves, nullptr, st);
     if (e == hipSuccess) {
       k_relocate<<<dim3((unsigned)(n_moves * chunks)), dim3(kMoveThreads), 0, st>>>(
           (u32x4*)weights_dev, (const u32x4*)backup_dev, slot_vecs, (int)chunks, c->mv_dst,
@@ -150,7 +155,7 @@ int eep_apply_repair(eep_ctx* c, void* weights, const void* backup, int64_t slot
     }
   }
   if (e != hipSuccess) return fail_hip(c, e);
-  return eep_update_placement(c, new_p2l, stream);
+  return publish_placement(c, new_p2l, true, st);
 }
 
 int eep_read_repair_outcome(eep_ctx* c, int32_t* outcome_host) {

@@ -7,10 +7,13 @@
 
 namespace eep {
 
+// version_dst (may be null): a word that counts the changes of the table; it is bumped on
+// the device, so that changes made by kernels (a rank dropped by the waiting kernel) and
+// changes made by the host share one count.
 __global__ __launch_bounds__(256) void k_patch(int32_t* __restrict__ dst, int n, PatchChunk chunk,
-                                               int32_t* version_dst, int32_t version) {
+                                               int32_t* version_dst) {
   for (int i = threadIdx.x; i < n; i += blockDim.x) dst[i] = chunk.v[i];
-  if (version_dst != nullptr && threadIdx.x == 0) *version_dst = version;
+  if (version_dst != nullptr && threadIdx.x == 0) *version_dst = *version_dst + 1;
 }
 
 __global__ __launch_bounds__(256) void k_fill(int32_t* __restrict__ dst, int32_t value, int64_t n) {
@@ -20,8 +23,8 @@ __global__ __launch_bounds__(256) void k_fill(int32_t* __restrict__ dst, int32_t
 }
 
 hipError_t launch_patch(int32_t* dst, const int32_t* src_host, int n, int32_t* version_dst,
-                        int32_t version, hipStream_t st) {
-  // The version word is written by the last chunk, after the data it describes.
+                        hipStream_t st) {
+  // The version word is bumped by the last chunk, after the data it describes.
   for (int done = 0; done < n || (n == 0 && done == 0); done += kPatchInts) {
     PatchChunk chunk;
     int m = n - done < kPatchInts ? n - done : kPatchInts;
@@ -29,7 +32,7 @@ hipError_t launch_patch(int32_t* dst, const int32_t* src_host, int n, int32_t* v
     for (int i = m; i < kPatchInts; ++i) chunk.v[i] = 0;
     bool last = done + kPatchInts >= n;
     hipLaunchKernelGGL(k_patch, dim3(1), dim3(256), 0, st, dst + done, m, chunk,
-                       last ? version_dst : nullptr, version);
+                       last ? version_dst : nullptr);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (n == 0) break;

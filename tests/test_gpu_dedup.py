@@ -111,6 +111,16 @@ def test_dedup_call_order_and_refusals():
         assert ei.value.code == binding.ERR_STATE
         ctx.dispatch_dedup(dev.x, other, wl.T)
         ctx.expand(other, dev.recv, wl.T)
+        # a new layout of the same T invalidates the de-duplicated tables of the old one
+        dev.layout()
+        with pytest.raises(binding.EepError) as ei:
+            ctx.dispatch_dedup(dev.x, other, wl.T)
+        assert ei.value.code == binding.ERR_STATE
+        with pytest.raises(binding.EepError) as ei:
+            ctx.expand(other, dev.recv, wl.T)
+        assert ei.value.code == binding.ERR_STATE
+        ctx.dedup_layout(wl.T)
+        ctx.dispatch_dedup(dev.x, other, wl.T)
         torch.cuda.synchronize()
     finally:
         ctx.destroy()

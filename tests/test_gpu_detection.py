@@ -17,15 +17,18 @@ TIMEOUT_NS = 200_000   # 200 us instead of the paper's 1 s
 SILENT = 6
 
 
-def _oracle_out(oracle, wl, p2l, active, drop_rank=None):
+def _oracle_out(oracle, wl, p2l, active, silent=()):
+    """One step of the oracle under the mask `active`, with the ranks in `silent`
+    sending no signal: layout, the rows the combine uses, the combined output, and what
+    the detection round leaves behind (mask for later steps, report for the host)."""
     lay = oracle.step_layout(wl.topk_idx, p2l, active, wl.E, wl.R, wl.S, wl.S_prim, oracle.SPREAD)
     recv = oracle.pack(wl.x, lay["row_of"])
     y = oracle.stub_scale(recv, oracle.BF16, lay["N"], lay["offset"], p2l, wl.expert_scale)
-    rows = lay["row_of"].copy()
-    if drop_rank is not None:               # pairs routed to the silent rank contribute nothing
-        rows[(lay["slot_of"] >= 0) & (lay["slot_of"] // wl.S == drop_rank)] = -1
-    chain = oracle.f32_to_bf16(oracle.combine_chain32(y, oracle.BF16, wl.topk_w, rows))
-    return lay, rows, chain
+    arrived = np.ones(wl.R, np.int32)
+    arrived[list(silent)] = 0
+    det = oracle.detect_round(lay["slot_of"], lay["row_of"], active, arrived, wl.S)
+    chain = oracle.f32_to_bf16(oracle.combine_chain32(y, oracle.BF16, wl.topk_w, det["row_of"]))
+    return lay, det, chain
 
 
 @pytest.mark.parametrize("T_batch", [512, 64])   # tiled layout / single-workgroup layout
@@ -57,41 +60,61 @@ def test_silent_rank_is_dropped_by_the_kernel(oracle, use_graph, T_batch):
         live = wl.active
         dead = synth.active_mask(R, (SILENT,))
         # 1. healthy step: every rank signals, nothing is dropped
-        lay, rows, chain = _oracle_out(oracle, wl, wl.p2l, live)
+        lay, det, chain = _oracle_out(oracle, wl, wl.p2l, live)
         got, out = run_and_read()
         gu.assert_layout_equal(got, lay, T, k)
         assert np.array_equal(out, chain)
         assert ctx.read_failures(stream).sum() == 0
         assert ctx.read("active", R, stream).tolist() == [1] * R
+        version = got["version"]
 
         # 2. rank SILENT stops signalling: the combine-side wait times out
         w = np.zeros(R, np.int32)
         w[SILENT] = 1
         ctx.debug_withhold_signal(w, stream)
-        lay, rows, chain = _oracle_out(oracle, wl, wl.p2l, live, drop_rank=SILENT)
+        lay, det, chain = _oracle_out(oracle, wl, wl.p2l, live, silent=(SILENT,))
         got, out = run_and_read()
         assert np.array_equal(got["slot_of"], lay["slot_of"])      # routed before the failure
-        assert np.array_equal(got["row_of"], rows)                 # its pairs lost their row
+        assert np.array_equal(got["row_of"], det["row_of"])        # its pairs lost their row
         assert np.array_equal(out, chain)
-        assert (rows == -1).sum() == lay["rank_count"][SILENT] > 0
+        assert det["withdrawn"] == lay["rank_count"][SILENT] > 0
+        assert det["active"].tolist() == dead.tolist()
         assert ctx.read("active", R, stream).tolist() == dead.tolist()   # cleared by the kernel
+        assert got["version"] == version       # this step's layout ran before the drop
 
         # 3. next step, no host action on the tables yet: routing already avoids the rank;
         #    experts that lived only there are uncovered and counted
-        lay, rows, chain = _oracle_out(oracle, wl, wl.p2l, dead)
+        lay, det, chain = _oracle_out(oracle, wl, wl.p2l, dead, silent=(SILENT,))
+        assert det["report"].sum() == 0            # a rank that is no longer active is not awaited
         got, out = run_and_read()
         gu.assert_layout_equal(got, lay, T, k)
         assert got["rank_count"][SILENT] == 0 and got["n_uncovered"] > 0
         assert np.array_equal(out, chain)
+        assert got["version"] == version + 1       # the drop shows in the table version
+
+        # until the host has read the report its copy of the mask is out of date: a membership
+        # update (here: another rank toggled) is refused rather than bringing the rank back
+        other = synth.active_mask(R, (SILENT + 1,))
+        with pytest.raises(binding.EepError) as ei:
+            ctx.set_membership(other, stream)
+        assert ei.value.code == binding.ERR_STATE
+        with pytest.raises(binding.EepError) as ei:     # strict context: coverage needs the mask
+            ctx.update_placement(wl.p2l, stream)
+        assert ei.value.code == binding.ERR_STATE
+        assert ctx.read("active", R, stream).tolist() == dead.tolist()
 
         # 4. the host learns of it, repairs the placement, service is complete again
         failed = ctx.read_failures(stream)
         assert failed.tolist() == w.tolist()
         assert ctx.read_failures(stream).sum() == 0                # report was cleared
+        # the placement that was fine a moment ago is now refused for what it is: uncovered
+        with pytest.raises(binding.EepError) as ei:
+            ctx.update_placement(wl.p2l, stream)
+        assert ei.value.code == binding.ERR_COVERAGE
         plan = binding.plan_repair(wl.p2l, dead, R, wl.S, wl.S_prim, wl.E)
         assert plan["unplaced"] == 0
         ctx.update_placement(plan["p2l"], stream)                  # passes the coverage check
-        lay, rows, chain = _oracle_out(oracle, wl, plan["p2l"], dead)
+        lay, det, chain = _oracle_out(oracle, wl, plan["p2l"], dead, silent=(SILENT,))
         got, out = run_and_read()
         gu.assert_layout_equal(got, lay, T, k)
         assert got["n_uncovered"] == 0 and got["N"] == T * k
@@ -99,9 +122,10 @@ def test_silent_rank_is_dropped_by_the_kernel(oracle, use_graph, T_batch):
 
         # 5. rejoin: the rank signals again, mask then preferred placement
         ctx.debug_withhold_signal(np.zeros(R, np.int32), stream)
+        assert ctx.read_failures(stream).sum() == 0                # the host is up to date
         ctx.set_membership(live, stream)
         ctx.update_placement(wl.p2l, stream)
-        lay, rows, chain = _oracle_out(oracle, wl, wl.p2l, live)
+        lay, det, chain = _oracle_out(oracle, wl, wl.p2l, live)
         got, out = run_and_read()
         gu.assert_layout_equal(got, lay, T, k)
         assert np.array_equal(out, chain)

@@ -251,17 +251,22 @@ def test_prefill_fp8_reduced(oracle):
     assert got["rank_count"][7] == 0 and got["rank_count"][20] == 0
 
 
-def test_prefill_fp8_full_size_sampled(oracle):
+def test_prefill_fp8_full_size_every_token(oracle):
     """Prefill shape at full size (T=16384, fp8 payload + scales, two failed
-    ranks).  Layout compared in full; moved rows checked in full against a torch
-    gather (a library routine for the same permutation); stub and combine
-    compared with the oracle on 256 sampled tokens."""
+    ranks).  Layout compared in full.  Then every token goes through the oracle
+    in chunks of 1024: the oracle packs the chunk's tokens into a compact receive
+    buffer (row c of it is the chunk's c-th routed pair), dequantises and
+    combines; the GPU's rows at row_of[chunk] must equal the compact rows byte
+    for byte (payload, scales, dequantised rows) and the combined rows must be
+    bit-equal to the fp32 chain.  Together the chunks cover all 131072 rows."""
     wl = synth.prefill_fp8()
     T, k, H = wl.T, wl.k, wl.H
     ctx = gu.make_context(wl)
     try:
         gu.apply_tables(ctx, wl.p2l, wl.active)
         dev = gu.DeviceStep(ctx, wl)
+        dev.recv.fill_(0x55)                    # nothing may survive from the buffers' fill
+        dev.y.fill_(0x5555)
         dev.step()
         dev.sync()
         lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim, 0)
@@ -269,28 +274,33 @@ def test_prefill_fp8_full_size_sampled(oracle):
         gu.assert_layout_equal(got, lay, T, k)
         N = got["N"]
         assert N == T * k and got["rank_count"][7] == 0 and got["rank_count"][20] == 0
-        src_tok = torch.from_numpy(lay["src_of"][:N] // k).cuda().long()
-        assert torch.equal(dev.recv[:N], dev.x.index_select(0, src_tok)), "packed fp8 rows"
-        assert torch.equal(dev.recv_scale[:N].view(torch.int32),
-                           dev.x_scale.index_select(0, src_tok).view(torch.int32)), "scale rows"
-        del src_tok
-        # sampled tokens: compact sub-problem for the oracle
-        rng = np.random.default_rng(8)
-        toks = np.sort(rng.choice(T, 256, replace=False))
-        rows = lay["row_of"][toks]                                    # [256, k], all routed
-        compact = np.arange(rows.size, dtype=np.int32).reshape(rows.shape)
-        recv_c = oracle.pack(wl.x[toks], compact)
-        scale_c = oracle.pack(wl.x_scale[toks], compact)
-        y_c = oracle.stub_dequant(recv_c, scale_c, rows.size, 128)
-        rows_dev = torch.from_numpy(rows.ravel()).cuda().long()
-        assert np.array_equal(dev.recv.index_select(0, rows_dev).cpu().numpy(), recv_c)
-        y_got = gu.to_host(dev.y.index_select(0, rows_dev), np.uint16)
-        assert np.array_equal(y_got, y_c), "dequantised rows"
-        out64 = oracle.combine(y_c, oracle.BF16, wl.topk_w[toks], compact)
-        chain = oracle.f32_to_bf16(oracle.combine_chain32(y_c, oracle.BF16, wl.topk_w[toks], compact))
-        out_got = gu.to_host(dev.out.index_select(0, torch.from_numpy(toks).cuda().long()), np.uint16)
-        gu.check_combine(out_got, "bf16", out64)
-        assert np.array_equal(out_got, chain)
+        seen = np.zeros(N, bool)
+        chunk = 1024
+        for t0 in range(0, T, chunk):
+            toks = np.arange(t0, t0 + chunk)
+            rows = lay["row_of"][toks]                                # [chunk, k], all routed
+            assert (rows >= 0).all()
+            seen[rows.ravel()] = True
+            compact = np.arange(rows.size, dtype=np.int32).reshape(rows.shape)
+            recv_c = oracle.pack(wl.x[toks], compact)
+            scale_c = oracle.pack(wl.x_scale[toks], compact)
+            y_c = oracle.stub_dequant(recv_c, scale_c, rows.size, 128)
+            rows_dev = torch.from_numpy(rows.ravel()).cuda().long()
+            assert np.array_equal(dev.recv.index_select(0, rows_dev).cpu().numpy(), recv_c), \
+                f"packed fp8 rows, tokens from {t0}"
+            assert np.array_equal(dev.recv_scale.index_select(0, rows_dev).cpu().numpy()
+                                  .view(np.uint32), scale_c.view(np.uint32)), \
+                f"scale rows, tokens from {t0}"
+            y_got = gu.to_host(dev.y.index_select(0, rows_dev), np.uint16)
+            assert np.array_equal(y_got, y_c), f"dequantised rows, tokens from {t0}"
+            out64 = oracle.combine(y_c, oracle.BF16, wl.topk_w[toks], compact)
+            chain = oracle.f32_to_bf16(oracle.combine_chain32(y_c, oracle.BF16, wl.topk_w[toks],
+                                                              compact))
+            out_got = gu.to_host(dev.out[t0:t0 + chunk], np.uint16)
+            gu.check_combine(out_got, "bf16", out64)
+            assert np.array_equal(out_got, chain), f"combined rows, tokens from {t0}"
+            print(f"prefill parity: tokens {t0}..{t0 + chunk - 1} ok", flush=True)
+        assert seen.all()                       # the chunks' rows are all N rows of the buffer
     finally:
         ctx.destroy()
 

@@ -65,8 +65,48 @@ def _check_plan(out, cur, active, R, S, S_prim, E):
         else:
             assert kind[p] == ref.DRAM
             assert not ((cur == new[p]) & live).any()                  # no GPU-resident copy left
-    # never fewer live copies than before for an expert that was not evicted for coverage
+    # What Sec. 3.5 fixes without naming an algorithm.  (1) Nothing that is already in
+    # place is moved: a live slot that keeps its expert is local reuse, never a copy.
+    keeps = live & (new == cur) & (cur >= 0)
+    assert (kind[keeps] == ref.LOCAL).all()
+    # (2) The backup tier is used exactly for the experts that lost every GPU copy, once
+    # each: that is the least movement that restores coverage.
+    lost = [e for e in range(E) if not ((cur == e) & live).any()]
+    from_dram = sorted(new[kind == ref.DRAM].tolist())
+    assert len(from_dram) == len(set(from_dram)) == len(lost) - out["unplaced"]
+    assert set(from_dram) <= set(lost)
+    # (3) An expert that had a live copy still has one (coverage never regresses).
+    had_live = set(cur[live].tolist()) - {-1}
+    assert had_live <= covered
     return covered
+
+
+def _brute_force_best(cur, active, R, S, E):
+    """All ways to fill the live slots: the best reachable coverage and the fewest slots
+    that must be rewritten to reach it."""
+    import itertools
+    P = R * S
+    live = [p for p in range(P) if active[p // S]]
+    best = (-1, 0)
+    for choice in itertools.product(range(-1, E), repeat=len(live)):
+        covered = len(set(choice) - {-1})
+        rewrites = sum(1 for p, e in zip(live, choice) if e != cur[p])
+        best = max(best, (covered, -rewrites))
+    return best[0], -best[1]
+
+
+@pytest.mark.parametrize("impl", sorted(IMPLS))
+def test_coverage_is_maximal_and_backup_movement_minimal_by_brute_force(impl):
+    rng = np.random.default_rng(2024)
+    for trial in range(120):
+        R, S = int(rng.integers(1, 4)), int(rng.integers(1, 3))
+        E = int(rng.integers(1, 5))
+        cur = rng.integers(-1, E, size=R * S).astype(np.int32)
+        active = (rng.random(R) < 0.7).astype(np.int32)
+        out = IMPLS[impl](cur, active, R, S, int(rng.integers(0, S + 1)), E)
+        best_cov, min_rewrites = _brute_force_best(cur.tolist(), active.tolist(), R, S, E)
+        assert E - out["unplaced"] == best_cov, (trial, cur, active)
+        assert out["dram"] == min_rewrites, (trial, cur, active)
 
 
 @pytest.mark.parametrize("seed", range(6))
@@ -86,6 +126,7 @@ def test_library_matches_plain_statement_and_invariants(seed):
         assert (a["local"], a["peer"], a["dram"], a["unplaced"]) == \
                (b["local"], b["peer"], b["dram"], b["unplaced"])
         _check_plan(a, cur, active, R, S, S_prim, E)
+        _check_plan(b, cur, active, R, S, S_prim, E)
         # pigeonhole: coverage is reached exactly when the live slots can hold E experts
         live_slots = int(active.sum()) * S
         assert a["unplaced"] == max(0, E - live_slots)
