@@ -79,29 +79,72 @@ __global__ __launch_bounds__(64) void k_pack(const u32x4* __restrict__ x,
   }
 }
 
-// Scale rows of fp8 payloads (H/group fp32 values, 224 bytes at the prefill
-// shape), moved by a launch of their own.  These small scattered writes are
-// expensive next to the payload stream (~25 us for 29 MB at T=16384, measured
-// by leaving them out); a separate launch was a few us faster than issuing them
-// from inside k_pack and keeps that kernel free of partial-wavefront stores.
-__global__ __launch_bounds__(64) void k_pack_scales(const u32x4* __restrict__ x_scale,
-                                                    u32x4* __restrict__ recv_scale,
-                                                    const int32_t* __restrict__ row_of, int k,
-                                                    int scale_vecs) {
-  const int t = blockIdx.x;
-  const int32_t* rows = row_of + (int64_t)t * k;
-  for (int v = threadIdx.x; v < scale_vecs; v += 64) {
-    u32x4 s = __builtin_nontemporal_load(&x_scale[(int64_t)t * scale_vecs + v]);
+// Several tokens per wavefront: all TPW * U loads of the wavefront are issued
+// before its first store, then the TPW * k rows stream out.  Measured on MI355X
+// (T = 16384, 7 KiB rows): 212 us with one token per wavefront, 201 with four,
+// 192 with eight; what counts is that the launch comes down to about 2048
+// wavefronts -- two per SIMD, all resident at once, every load of the launch in
+// flight before the stores start.  Fewer wavefronts than that, or a loop over
+// token groups inside a wavefront, are slower again.  T % TPW == 0, rows exact.
+template <int U, int TPW>
+__global__ __launch_bounds__(64) void k_pack_multi(const u32x4* __restrict__ x,
+                                                   u32x4* __restrict__ recv,
+                                                   const int32_t* __restrict__ row_of, int k,
+                                                   int row_vecs) {
+  const int t0 = blockIdx.x * TPW;
+  const int lane = threadIdx.x;
+  u32x4 buf[TPW][U];
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+    const u32x4* src = x + (int64_t)(t0 + q) * row_vecs;
+#pragma unroll
+    for (int u = 0; u < U; ++u) buf[q][u] = __builtin_nontemporal_load(&src[u * 64 + lane]);
+  }
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) asm volatile("" ::"v"(buf[q][u]));  // waits sit before the stores
+  }
+#pragma unroll
+  for (int q = 0; q < TPW; ++q) {
+    const int32_t* rows = row_of + (int64_t)(t0 + q) * k;
     for (int j = 0; j < k; ++j) {
       int row = rows[j];
-      if (row >= 0) recv_scale[(int64_t)row * scale_vecs + v] = s;
+      if (row < 0) continue;
+      u32x4* dst = recv + (int64_t)row * row_vecs;
+#pragma unroll
+      for (int u = 0; u < U; ++u) store_through(&dst[u * 64 + lane], buf[q][u]);
     }
   }
 }
 
+// Scale rows of fp8 payloads (H/group fp32 values per row; 224 bytes at the
+// prefill shape), written in DESTINATION order: a thread owns one 16-byte
+// vector of the receive scale buffer, finds the token behind its row through
+// src_of, and copies the vector from the small [T][H/group] source table (3.6 MB
+// at T = 16384, read 8 times, from cache).  All stores are contiguous.
+// Measured at T = 16384 inside the step (payload, scales, combine in a loop):
+// token-ordered scatter with one token per wavefront +27 us, with four tokens
+// per wavefront +20 us, this form +13 us, for 33 MB; 224-byte rows scattered
+// among the payload's write stream are what is expensive, not the launch.
+constexpr int kScaleThreads = 256;
+
+__global__ __launch_bounds__(kScaleThreads) void k_scale_rows(
+    const u32x4* __restrict__ x_scale, u32x4* __restrict__ recv_scale,
+    const int32_t* __restrict__ src_of, const int32_t* __restrict__ status, int k, int scale_vecs) {
+  const int64_t v = (int64_t)blockIdx.x * kScaleThreads + threadIdx.x;
+  const int64_t n_vecs = (int64_t)status[0] * scale_vecs;  // rows >= N are left untouched
+  if (v >= n_vecs) return;
+  const int row = (int)(v / scale_vecs);
+  const int col = (int)(v - (int64_t)row * scale_vecs);
+  const int pair = src_of[row];
+  if (pair < 0) return;
+  store_through(&recv_scale[v], x_scale[(int64_t)(pair / k) * scale_vecs + col]);
+}
+
 template <int U, bool EXACT>
-static hipError_t launch_pack_t(eep_ctx* c, const int32_t* rows, const void* x, const float* x_scale,
-                                void* recv_x, float* recv_scale, int T, int parts, hipStream_t st) {
+static hipError_t launch_pack_t(eep_ctx* c, const int32_t* rows, const void* x, void* recv_x,
+                                int T, int parts, hipStream_t st) {
   if (parts > 1)
     hipLaunchKernelGGL((k_pack<U, EXACT, true>), dim3((unsigned)((int64_t)T * parts)), dim3(64), 0,
                        st, (const u32x4*)x, (u32x4*)recv_x, rows, c->k,
@@ -109,17 +152,26 @@ static hipError_t launch_pack_t(eep_ctx* c, const int32_t* rows, const void* x, 
   else
     hipLaunchKernelGGL((k_pack<U, EXACT, false>), dim3(T), dim3(64), 0, st, (const u32x4*)x,
                        (u32x4*)recv_x, rows, c->k, (int)(c->x_row_bytes / 16), 1);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || x_scale == nullptr) return e;
-  hipLaunchKernelGGL(k_pack_scales, dim3(T), dim3(64), 0, st, (const u32x4*)x_scale,
-                     (u32x4*)recv_scale, c->row_of, c->k, (int)(c->scale_row_bytes / 16));
   return hipGetLastError();
 }
 
-static hipError_t launch_pack_any(eep_ctx* c, const int32_t* rows, const void* x,
-                                  const float* x_scale, void* recv_x, float* recv_scale, int T,
-                                  hipStream_t st) {
-  if (T == 0) return hipSuccess;
+template <int U, int TPW>
+static hipError_t launch_pack_multi_t(eep_ctx* c, const int32_t* rows, const void* x, void* recv_x,
+                                      int T, hipStream_t st) {
+  hipLaunchKernelGGL((k_pack_multi<U, TPW>), dim3(T / TPW), dim3(64), 0, st, (const u32x4*)x,
+                     (u32x4*)recv_x, rows, c->k, (int)(c->x_row_bytes / 16));
+  return hipGetLastError();
+}
+
+// Below 8192 tokens one wavefront per token already fits the chip in one round (8192
+// resident wavefronts), and at the decode shape (T = 4096, 14 KiB rows) two tokens per
+// wavefront made the step 3 us slower: pack itself no faster, the combine after it slower.
+constexpr int kPackMultiMinTokens = 8192;
+constexpr int kPackMultiMinWaves = 2048;  // two wavefronts per SIMD of the 256 CUs
+constexpr int kPackMultiMaxVecs = 56;     // 16-byte vectors a lane holds at once
+
+static hipError_t launch_pack_payload(eep_ctx* c, const int32_t* rows, const void* x, void* recv_x,
+                                      int T, hipStream_t st) {
   const int row_vecs = (int)(c->x_row_bytes / 16);
   if (row_vecs % 64 == 0) {
     // Large batches: one wavefront per token, the largest pass width <= kPackVecs that
@@ -140,17 +192,58 @@ static hipError_t launch_pack_any(eep_ctx* c, const int32_t* rows, const void* x
       u = kPackVecs;
       while (per_lane % u != 0) --u;
       parts = 1;
+      // Very large batches (>= kPackMultiMinTokens) of whole-row passes: several tokens per
+      // wavefront, as many as keep >= kPackMultiMinWaves wavefronts and <= kPackMultiMaxVecs
+      // vectors per lane.
+      if (u == per_lane) {
+        int tpw = 1;
+        while (T >= kPackMultiMinTokens && tpw < 8 && T % (tpw * 2) == 0 &&
+               T / (tpw * 2) >= kPackMultiMinWaves &&
+               per_lane * tpw * 2 <= kPackMultiMaxVecs)
+          tpw *= 2;
+        if (tpw > 1) {
+          switch (tpw * 16 + u) {
+#define EEP_PACK_MULTI(TPW, U) \
+  case TPW * 16 + U: return launch_pack_multi_t<U, TPW>(c, rows, x, recv_x, T, st);
+            EEP_PACK_MULTI(2, 1) EEP_PACK_MULTI(2, 2) EEP_PACK_MULTI(2, 3) EEP_PACK_MULTI(2, 4)
+            EEP_PACK_MULTI(2, 5) EEP_PACK_MULTI(2, 6) EEP_PACK_MULTI(2, 7) EEP_PACK_MULTI(2, 8)
+            EEP_PACK_MULTI(2, 9) EEP_PACK_MULTI(2, 10) EEP_PACK_MULTI(2, 11) EEP_PACK_MULTI(2, 12)
+            EEP_PACK_MULTI(2, 13) EEP_PACK_MULTI(2, 14)
+            EEP_PACK_MULTI(4, 1) EEP_PACK_MULTI(4, 2) EEP_PACK_MULTI(4, 3) EEP_PACK_MULTI(4, 4)
+            EEP_PACK_MULTI(4, 5) EEP_PACK_MULTI(4, 6) EEP_PACK_MULTI(4, 7) EEP_PACK_MULTI(4, 8)
+            EEP_PACK_MULTI(4, 9) EEP_PACK_MULTI(4, 10) EEP_PACK_MULTI(4, 11) EEP_PACK_MULTI(4, 12)
+            EEP_PACK_MULTI(4, 13) EEP_PACK_MULTI(4, 14)
+            EEP_PACK_MULTI(8, 1) EEP_PACK_MULTI(8, 2) EEP_PACK_MULTI(8, 3) EEP_PACK_MULTI(8, 4)
+            EEP_PACK_MULTI(8, 5) EEP_PACK_MULTI(8, 6) EEP_PACK_MULTI(8, 7)
+#undef EEP_PACK_MULTI
+          }
+        }
+      }
     }
     switch (u) {
 #define EEP_PACK_CASE(U) \
-  case U: return launch_pack_t<U, true>(c, rows, x, x_scale, recv_x, recv_scale, T, parts, st);
+  case U: return launch_pack_t<U, true>(c, rows, x, recv_x, T, parts, st);
       EEP_PACK_CASE(14) EEP_PACK_CASE(13) EEP_PACK_CASE(12) EEP_PACK_CASE(11) EEP_PACK_CASE(10)
       EEP_PACK_CASE(9) EEP_PACK_CASE(8) EEP_PACK_CASE(7) EEP_PACK_CASE(6) EEP_PACK_CASE(5)
       EEP_PACK_CASE(4) EEP_PACK_CASE(3) EEP_PACK_CASE(2) EEP_PACK_CASE(1)
 #undef EEP_PACK_CASE
     }
   }
-  return launch_pack_t<kPackVecs, false>(c, rows, x, x_scale, recv_x, recv_scale, T, 1, st);
+  return launch_pack_t<kPackVecs, false>(c, rows, x, recv_x, T, 1, st);
+}
+
+static hipError_t launch_pack_any(eep_ctx* c, const int32_t* rows, const void* x,
+                                  const float* x_scale, void* recv_x, float* recv_scale, int T,
+                                  hipStream_t st) {
+  if (T == 0) return hipSuccess;
+  hipError_t e = launch_pack_payload(c, rows, x, recv_x, T, st);
+  if (e != hipSuccess || x_scale == nullptr) return e;
+  const int scale_vecs = (int)(c->scale_row_bytes / 16);
+  const int64_t vecs = (int64_t)T * c->k * scale_vecs;
+  hipLaunchKernelGGL(k_scale_rows, dim3((unsigned)((vecs + kScaleThreads - 1) / kScaleThreads)),
+                     dim3(kScaleThreads), 0, st, (const u32x4*)x_scale, (u32x4*)recv_scale,
+                     c->src_of, c->status, c->k, scale_vecs);
+  return hipGetLastError();
 }
 
 hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
