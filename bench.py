@@ -23,10 +23,77 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch at this workload from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each
-# scaled by the same counter's reading for the 512 MiB k_calibration_copy
-# (profiles/dsv3_decode_hbm_traffic.md).
-HBM_TRAFFIC_BYTES = {"k_pack": 59259849 + 469762048, "k_combine": 474030997 + 58720256}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, each scaled by the
+# same counter's reading for the 512 MiB k_calibration_copy.  The file is written by
+# `bench.py --traffic-from FETCH.csv WRITE.csv --workload W` when the counters are
+# refreshed and records a hash of the kernel sources it was measured with; figures taken
+# with other sources are not reported.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+CALIB_BYTES = 512 << 20
+STAGE_KERNELS = {"dispatch": ("k_pack", "k_pack_multi", "k_pack_quant", "k_scale_rows"),
+                 "combine": ("k_combine",)}
+
+
+def source_hash():
+    """Hash of the HIP sources the library is built from (the built .so travels with them)."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2605_10670_amd", "csrc", "*"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def load_traffic(workload):
+    """{stage: HBM bytes per launch} measured with the current sources, or {}."""
+    try:
+        entry = json.load(open(TRAFFIC_FILE))["workloads"][workload]
+    except (OSError, KeyError, ValueError):
+        return {}
+    if entry.get("source_hash") != source_hash():
+        return {}
+    return {st: v["fetch_bytes"] + v["write_bytes"] for st, v in entry["stages"].items()}
+
+
+def write_traffic(workload, fetch_csv, write_csv):
+    """Turn two rocprofv3 --pmc counter_collection.csv files (FETCH_SIZE, WRITE_SIZE; runs of
+    `bench.py --calib --mode eager`) into the workload's entry of profiles/hbm_traffic.json."""
+    import csv
+    import re
+
+    def per_kernel(path, counter):
+        acc = {}
+        for row in csv.DictReader(open(path)):
+            if row["Counter_Name"] != counter:
+                continue
+            m = re.search(r"eep::(k_\w+)", row["Kernel_Name"])
+            if m:
+                a = acc.setdefault(m.group(1), [0, 0.0])
+                a[0] += 1
+                a[1] += float(row["Counter_Value"])
+        return acc
+
+    fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
+    scale = {}
+    for name, acc in (("FETCH_SIZE", fetch), ("WRITE_SIZE", write)):
+        n, total = acc["k_calibration_copy"]
+        scale[name] = (CALIB_BYTES / 1024) / (total / n)      # true KiB per counted KiB
+    stages = {}
+    for stage, kernels in STAGE_KERNELS.items():
+        steps = max(fetch.get("k_combine", [1])[0], 1)          # one combine launch per step
+        kib = lambda acc: sum(acc[k][1] for k in kernels if k in acc) / steps
+        stages[stage] = {"fetch_bytes": round(kib(fetch) * scale["FETCH_SIZE"] * 1024),
+                         "write_bytes": round(kib(write) * scale["WRITE_SIZE"] * 1024),
+                         "kernels": sorted(k for k in kernels if k in fetch)}
+    try:
+        doc = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        doc = {"workloads": {}}
+    doc["workloads"][workload] = {"source_hash": source_hash(), "counter_scale": scale,
+                                  "stages": stages}
+    json.dump(doc, open(TRAFFIC_FILE, "w"), indent=1, sort_keys=True)
+    print(json.dumps(doc["workloads"][workload]))
 
 
 def algorithmic_bytes(T, k, H, x_bytes, y_bytes, out_bytes, scale_row_bytes=0):
@@ -54,40 +121,71 @@ def time_events(stream, fn, reps):
     return e0.elapsed_time(e1) / reps  # ms
 
 
-def cpu_baseline(wl, bytes_total, quant=False, budget_s=20.0):
-    """The oracle as it stands (single thread) on the same workload: the same
-    three calls as the GPU step (layout, pack, combine); y comes from outside."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(wl, bytes_total, quant=False, budget_s=12.0):
+    """The oracle as it stands on the same workload: the same three calls as the GPU step
+    (layout, pack, combine; y comes from outside).  Two legs: one thread, and the row copies
+    and the combine split over the host cores by token range (threads around the same C
+    functions, which release the interpreter lock; the layout stays serial)."""
+    import concurrent.futures as cf
+    import numpy as np
     import oracle
     ydt = oracle.BF16 if wl.y_dtype == "bf16" else oracle.F32
-    lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim,
-                             oracle.SPREAD)
-    if wl.stub == "identity":
-        y = None
-    else:  # expert stand-in output, prepared outside the timed region like on the GPU
-        import numpy as np
-        y = np.zeros((wl.T * wl.k, wl.H), np.uint16 if wl.y_dtype == "bf16" else np.float32)
-    times = []
-    t_all = time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < 10):
-        t0 = time.perf_counter()
+    T = wl.T
+    y_ext = None
+    if wl.stub != "identity":   # expert stand-in output, prepared outside the timed region like on the GPU
+        y_ext = np.zeros((T * wl.k, wl.H), np.uint16 if wl.y_dtype == "bf16" else np.float32)
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+
+    def one_step(pool, workers):
         lay = oracle.step_layout(wl.topk_idx, wl.p2l, wl.active, wl.E, wl.R, wl.S, wl.S_prim,
                                  oracle.SPREAD)
+        rows = lay["row_of"]
+        bounds = [T * i // workers for i in range(workers + 1)]
+        ranges = [(a, b) for a, b in zip(bounds, bounds[1:]) if b > a]
+        x, xs = wl.x, wl.x_scale
         if quant:
-            q, sc = oracle.quantize_e4m3(wl.x, 128)
-            recv = oracle.pack(q, lay["row_of"])
-            oracle.pack(sc, lay["row_of"])
-        else:
-            recv = oracle.pack(wl.x, lay["row_of"])
-        if wl.x_scale is not None:
-            oracle.pack(wl.x_scale, lay["row_of"])
-        oracle.combine(recv if y is None else y, ydt, wl.topk_w, lay["row_of"])
-        times.append(time.perf_counter() - t0)
-        if time.perf_counter() - t_all > budget_s:
-            break
-    med = statistics.median(times)
-    return {"value": bytes_total / med / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "ms_per_step": med * 1e3,
-            "sample": f"{len(times)} full {wl.name} steps (T={wl.T}), median"}
+            q_sc = list(pool.map(lambda r: oracle.quantize_e4m3(wl.x[r[0]:r[1]], 128), ranges))
+            x = np.concatenate([q for q, _ in q_sc])
+            xs = np.concatenate([sc for _, sc in q_sc])
+        recv = np.empty((T * wl.k,) + x.shape[1:], x.dtype)
+        list(pool.map(lambda r: oracle.pack_into(x[r[0]:r[1]], rows[r[0]:r[1]], recv), ranges))
+        if xs is not None:
+            rs = np.empty((T * wl.k,) + xs.shape[1:], xs.dtype)
+            list(pool.map(lambda r: oracle.pack_into(xs[r[0]:r[1]], rows[r[0]:r[1]], rs), ranges))
+        y = recv if y_ext is None else y_ext
+        list(pool.map(lambda r: oracle.combine(y, ydt, wl.topk_w[r[0]:r[1]], rows[r[0]:r[1]]),
+                      ranges))
+
+    def leg(workers):
+        with cf.ThreadPoolExecutor(workers) as pool:
+            one_step(pool, workers)                 # warm-up (page faults of the big buffers)
+            times, t_all = [], time.perf_counter()
+            while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < 10):
+                t0 = time.perf_counter()
+                one_step(pool, workers)
+                times.append(time.perf_counter() - t0)
+        med = statistics.median(times)
+        return {"value": bytes_total / med / 1e9, "unit": "GB/s", "cores": workers,
+                "ms_per_step": med * 1e3,
+                "sample": f"{len(times)} full {wl.name} steps (T={T}), median"}
+
+    single = leg(1)
+    out = leg(cores) if cores > 1 else dict(single)
+    out.update({"kind": "oracle", "cpu_model": cpu_model(), "host_cpus": os.cpu_count(),
+                "single_thread": single,
+                "note": "layout serial; row copies and combine split over `cores` threads by "
+                        "token range"})
+    return out
 
 
 WORKLOADS = {
@@ -102,6 +200,11 @@ WORKLOADS = {
     "decode_dedup": ("dsv3-decode with de-duplicated dispatch: T=4096, H=7168 bf16, one row per (token, "
                      "destination rank) (eep_dedup_layout + eep_dispatch_dedup); the expert stage is "
                      "taken to gather through expand_of, y prepared once by eep_expand, untimed"),
+    "decode_double_buffer": ("dsv3-decode with double-buffered staging: two micro-batches of T=4096 "
+                             "(H=7168 bf16, E=256, top-8, all live) alternate through two staging sets "
+                             "(eep_create_staging); the dispatch side of one runs on a side stream beside "
+                             "the combine of the other (eep_staging_fork / eep_staging_join); a pass of 8 "
+                             "steps is one hipGraph, drained at both ends"),
     "churn": "qwen3-moe-like: T=2048, H=4096 bf16, E=128, top-8, R=16, 8+1 slots/rank, all live",
     "repair": ("weight movement after a rank failure (eep_apply_repair; not the hot path): 32 ranks "
                "x (8+2) slots, one redundant slot empty, E=256, 44 MB per expert (three 7168x2048 "
@@ -173,6 +276,90 @@ def bench_repair(args, stream, copy_gbs):
                       "note": "kernel reads pinned host memory over the host link"},
     }))
     ctx.destroy()
+
+
+def bench_double_buffer(args, stream, copy_gbs):
+    """Two staging sets, dispatch of one micro-batch beside the combine of the other, against
+    the same 8 steps queued one after the other on one stream."""
+    import numpy as np
+    import torch
+    from paper_2605_10670_amd import binding, synth
+
+    wls = [synth.decode(seed_offset=2), synth.decode(seed_offset=12)]
+    wl = wls[0]
+    T, k, H = wl.T, wl.k, wl.H
+    side = torch.cuda.Stream()
+    ctx = [binding.Context(num_ranks=wl.R, slots_per_rank=wl.S, primary_slots=wl.S_prim,
+                           num_logical=wl.E, max_tokens=T, topk=k, hidden=H)]
+    ctx.append(ctx[0].staging())
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)
+                                     if a.dtype == np.uint16 else np.ascontiguousarray(a)).cuda()
+    idx, w, x = ([dev(getattr(v, n)) for v in wls] for n in ("topk_idx", "topk_w", "x"))
+    recv = [torch.empty((T * k, H), dtype=torch.int16, device="cuda") for _ in range(2)]
+    out = [torch.empty((T, H), dtype=torch.int16, device="cuda") for _ in range(2)]
+    ctx[0].update_placement(wl.p2l, stream)
+    ctx[0].set_membership(wl.active, stream)
+    steps_per_pass = 8
+
+    def d_side(s, st):
+        ctx[s].dispatch_layout(idx[s], T, st)
+        ctx[s].dispatch(x[s], recv[s], T, stream=st)
+
+    def c_side(s):
+        ctx[s].combine(recv[s], w[s], out[s], T, stream)
+
+    def overlapped():
+        d_side(0, stream)
+        for i in range(steps_per_pass):
+            s, nxt = i % 2, (i + 1) % 2
+            last = i + 1 == steps_per_pass
+            if not last:
+                ctx[nxt].staging_fork(idx[nxt], x[nxt], recv[nxt], T, stream, side)
+            c_side(s)
+            if not last:
+                ctx[nxt].staging_join(stream, side)
+
+    def sequential():
+        for i in range(steps_per_pass):
+            d_side(i % 2, stream)
+            c_side(i % 2)
+
+    result = {}
+    for name, fn in (("sequential", sequential), ("overlapped", overlapped)):
+        fn()
+        stream.synchronize()
+        ctx[0].graph_begin(stream)
+        fn()
+        g = ctx[0].graph_end(stream)
+        for _ in range(max(1, args.warmup // steps_per_pass)):
+            g.launch(stream)
+        stream.synchronize()
+        n_rep = max(25, args.steps // steps_per_pass)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(n_rep)]
+        for e in ev:
+            e[0].record(stream)
+            g.launch(stream)
+            e[1].record(stream)
+        stream.synchronize()
+        per = sorted(e[0].elapsed_time(e[1]) * 1e3 / steps_per_pass for e in ev)
+        result[name] = {"p10": per[n_rep // 10], "p50": per[n_rep // 2], "p90": per[(n_rep * 9) // 10],
+                        "replays": n_rep}
+        g.destroy()
+    nbytes = algorithmic_bytes(T, k, H, 2, 2, 2)["total"]
+    us = result["overlapped"]["p50"]
+    print(json.dumps({
+        "metric": "dispatch+combine achieved HBM GB/s (algorithmic bytes / step time), "
+                  "decode_double_buffer", "value": nbytes / us / 1e3, "unit": "GB/s", "n_gpus": 1,
+        "steps": result["overlapped"]["replays"] * steps_per_pass, "warmup": args.warmup,
+        "ms_per_step": us / 1e3, "us_per_step": us, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": WORKLOADS["decode_double_buffer"], "mode": "graph",
+                   "steps_per_graph": steps_per_pass, "algorithmic_bytes_per_step": nbytes},
+        "frac_of_hbm_peak": nbytes / us / 1e3 / HBM_PEAK_GBS, "copy_ceiling_gbs": copy_gbs,
+        "overlapped_us_per_step": result["overlapped"],
+        "sequential_us_per_step": result["sequential"]}))
+    ctx[1].destroy()
+    ctx[0].destroy()
 
 
 def bench_repair_scales(args, stream):
@@ -257,7 +444,13 @@ def main():
     ap.add_argument("--calib", action="store_true",
                     help="first launch 5 plain copy kernels of 512 MiB (k_calibration_copy), the "
                          "yardstick for rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: read two rocprofv3 --pmc counter_collection.csv files "
+                         "(FETCH_SIZE run, WRITE_SIZE run, both of `--calib --mode eager` for "
+                         "--workload) and record the HBM bytes per launch in profiles/hbm_traffic.json")
     args = ap.parse_args()
+    if args.traffic_from:
+        return write_traffic(args.workload, *args.traffic_from)
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (virtual EP ranks share one HBM); "
                  "use --gpus 1")
@@ -285,6 +478,8 @@ def main():
         return bench_repair(args, stream, copy_gbs)
     if args.workload == "repair_scales":
         return bench_repair_scales(args, stream)
+    if args.workload == "decode_double_buffer":
+        return bench_double_buffer(args, stream, copy_gbs)
 
     quant = args.workload == "decode_quant"
     dedup = args.workload == "decode_dedup"
@@ -446,6 +641,14 @@ def main():
     if graph is not None:
         graph.destroy()
 
+    # A handful of replays is a noisy clock: with fewer than 50 timed replays the headline is
+    # the median of the individually timed replays above (>= 200 of them); the mean over
+    # exactly --steps steps is reported beside it.
+    timed_ms = ms
+    timed_replays = args.steps // spg if graph is not None else args.steps
+    if replay_pct is not None and timed_replays < 50:
+        ms = replay_pct["p50"] / 1e3
+    traffic = load_traffic(args.workload) if not args.tokens else {}
     kernel_of = {"dispatch": "k_pack_quant" if quant else "k_pack", "combine": "k_combine"}
     # (with de-duplication the layout stage holds four launches and the dispatch stage k_pack)
     event_cost_ms = max(0.0, (sum(stage_ms.values()) - other_ms) / 3)
@@ -461,9 +664,7 @@ def main():
         kernels[kname] = {"avg_launch_us": launch_ms * 1e3,
                           "algorithmic_bytes_per_launch": nbytes[stage], "achieved": gbs,
                           "frac": gbs / HBM_PEAK_GBS,
-                          "traffic": HBM_TRAFFIC_BYTES.get(kname)
-                          if args.workload == "decode" and not args.tokens
-                          else None}
+                          "traffic": traffic.get(stage)}
     dom = max(kernels, key=lambda n: kernels[n]["avg_launch_us"])
     result = {
         "metric": "dispatch+combine achieved HBM GB/s (algorithmic bytes / step time), "
@@ -472,6 +673,9 @@ def main():
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "us_per_step": ms * 1e3,
+        "ms_per_step_is": ("median of %d individually timed graph replays" % replay_pct["replays"]
+                           if ms != timed_ms else "mean over exactly --steps steps"),
+        "timed_ms_per_step": timed_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "u8"}[wl.x_dtype], "data": "synthetic",
         "config": {"workload": WORKLOADS[args.workload] if not args.tokens else
@@ -492,6 +696,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": kernels[dom]["achieved"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels[dom]["frac"],
                      "traffic": kernels[dom]["traffic"],
+                     "traffic_source": ("profiles/hbm_traffic.json, sources " + source_hash()
+                                        if kernels[dom]["traffic"] else None),
                      "algorithmic_bytes_per_launch": kernels[dom]["algorithmic_bytes_per_launch"],
                      "avg_launch_us": kernels[dom]["avg_launch_us"]},
         "kernels": kernels,

@@ -130,7 +130,8 @@ int eep_create_attached(const eep_config* cfg, eep_ctx* parent, eep_ctx** out);
 /* Ends the lifetime of the stable pointers (Fig. 4, Fig. 8): graphs captured
  * with this context must not be replayed afterwards.  Waits for the device,
  * frees everything the context owns.  NULL is OK.
- * EEP_ERR_STATE if attached contexts of this instance still exist. */
+ * EEP_ERR_STATE if attached contexts of this instance, or staging contexts of
+ * this context, still exist. */
 int eep_destroy(eep_ctx* ctx);
 
 /* ---- table updates: between steps, stream-ordered (Sec. 3.1: repair and

@@ -91,6 +91,19 @@ def pack(x, row_of, fill=0):
     return recv
 
 
+def pack_into(x, row_of, recv):
+    """O6 into an existing receive buffer: recv[row_of[t, j]] = x[t] for the tokens given
+    (x and row_of may be a token range of a larger step; recv is the whole buffer)."""
+    x = np.ascontiguousarray(x)
+    row_of = _i32(row_of)
+    T, k = row_of.shape
+    assert recv.flags.c_contiguous and recv.dtype == x.dtype and recv.shape[1:] == x.shape[1:]
+    assert T == 0 or int(row_of.max()) < recv.shape[0]
+    row_bytes = x[0].nbytes if T else 0
+    lib().eeo_pack(T, k, ctypes.c_int64(row_bytes), _p(x), _p(row_of), _p(recv))
+    return recv
+
+
 def dedup_layout(slot_of, row_of, R, S):
     """De-duplicated dispatch layout -> dict(dedup_count, dedup_offset, dedup_row, lead, expand_of, N_d)."""
     slot_of, row_of = _i32(slot_of), _i32(row_of)

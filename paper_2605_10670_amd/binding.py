@@ -76,6 +76,9 @@ def load():
         "eep_workspace_bytes": [ctypes.POINTER(_Config), ctypes.POINTER(i64)],
         "eep_create_with_workspace": [ctypes.POINTER(_Config), vp, i64, ctypes.POINTER(vp)],
         "eep_create_attached": [ctypes.POINTER(_Config), vp, ctypes.POINTER(vp)],
+        "eep_create_staging": [vp, ctypes.POINTER(vp)],
+        "eep_staging_fork": [vp, vp, vp, vp, vp, vp, i32, vp, vp],
+        "eep_staging_join": [vp, vp, vp],
         "eep_destroy": [vp],
         "eep_set_membership": [vp, vp, vp],
         "eep_update_placement": [vp, vp, vp],
@@ -286,7 +289,8 @@ class Context:
 
     def __init__(self, *, num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk,
                  hidden, x_dtype="bf16", y_dtype="bf16", out_dtype="bf16", scale_group=None,
-                 policy=SPREAD, strict_coverage=True, parent=None, workspace=None):
+                 policy=SPREAD, strict_coverage=True, parent=None, workspace=None,
+                 _staging_of=None):
         xd = DTYPES[x_dtype] if isinstance(x_dtype, str) else x_dtype
         if scale_group is None:
             scale_group = 128 if xd == FP8_E4M3 else 0
@@ -297,7 +301,11 @@ class Context:
         self._h = ctypes.c_void_p()
         self._parent = parent      # keeps the instance's first context alive
         self._workspace = workspace    # caller-owned slab (a uint8 device tensor), kept alive
-        if workspace is not None:
+        if _staging_of is not None:
+            self._parent = _staging_of
+            _check(load().eep_create_staging(_staging_of._h, ctypes.byref(self._h)),
+                   "eep_create_staging")
+        elif workspace is not None:
             if parent is not None:
                 raise ValueError("workspace and parent cannot be combined")
             _check(load().eep_create_with_workspace(ctypes.byref(self.cfg), _ptr(workspace),
@@ -312,6 +320,27 @@ class Context:
         self.R, self.S, self.E, self.k = num_ranks, slots_per_rank, num_logical, topk
         self.P = num_ranks * slots_per_rank
         self.T_max = max_tokens
+
+    def staging(self):
+        """A second staging set of this layer (shared membership and placement tables,
+        own layout arrays): eep_create_staging."""
+        c = self.cfg
+        return Context(num_ranks=c.num_ranks, slots_per_rank=c.slots_per_rank,
+                       primary_slots=c.primary_slots, num_logical=c.num_logical,
+                       max_tokens=c.max_tokens, topk=c.topk, hidden=c.hidden, x_dtype=c.x_dtype,
+                       y_dtype=c.y_dtype, out_dtype=c.out_dtype, scale_group=c.scale_group,
+                       policy=c.policy, strict_coverage=bool(c.strict_coverage),
+                       _staging_of=self)
+
+    def staging_fork(self, topk_idx, x, recv_x, T, stream, side_stream, x_scale=None,
+                     recv_scale=None):
+        _check(load().eep_staging_fork(self._h, _ptr(topk_idx), _ptr(x), _ptr(x_scale),
+                                       _ptr(recv_x), _ptr(recv_scale), T, _stream(stream),
+                                       _stream(side_stream)), "eep_staging_fork", self._h)
+
+    def staging_join(self, stream, side_stream):
+        _check(load().eep_staging_join(self._h, _stream(stream), _stream(side_stream)),
+               "eep_staging_join", self._h)
 
     # -- table updates -------------------------------------------------------
     def set_membership(self, active, stream=None):

@@ -41,7 +41,7 @@ namespace {
 // One routine behind eep_create, eep_create_attached, eep_create_with_workspace and
 // eep_workspace_bytes (size_only: validate, report the slab size, touch no GPU).
 int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t workspace_bytes,
-                int64_t* size_only, eep_ctx** out) {
+                int64_t* size_only, eep_ctx** out, eep_ctx* staging_of = nullptr) {
   if (!out && !size_only) return EEP_ERR_INVALID_ARG;
   if (out) *out = nullptr;
   if (!cfg) return EEP_ERR_INVALID_ARG;
@@ -198,6 +198,9 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
     c->mem->unread_round = false;
   }
   c->active = c->mem->active;
+  c->tables = c;
+  c->n_staging = 0;
+  c->ev_fork = c->ev_join = nullptr;
   // initial state: every slot empty, nothing laid out
   c->h_p2l.assign(c->P, -1);
   hipStream_t st = nullptr;
@@ -214,6 +217,16 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
     if (!parent) delete c->mem;
     delete c;
     return EEP_ERR_HIP;
+  }
+  if (staging_of) {
+    // a second staging set of the same layer: the placement tables are the owner's
+    eep_ctx* owner = staging_of->tables;
+    c->tables = owner;
+    c->p2l = owner->p2l;
+    c->l2p_off = owner->l2p_off;
+    c->l2p_list = owner->l2p_list;
+    c->tbl_version = owner->tbl_version;
+    owner->n_staging += 1;
   }
   c->mem->members.push_back(c);
   *out = c;
@@ -251,12 +264,24 @@ int eep_create_attached(const eep_config* cfg, eep_ctx* parent, eep_ctx** out) {
   return create_impl(cfg, parent, nullptr, 0, nullptr, out);
 }
 
+int eep_create_staging(eep_ctx* of, eep_ctx** out) {
+  if (!of) {
+    if (out) *out = nullptr;
+    return EEP_ERR_INVALID_ARG;
+  }
+  return create_impl(&of->cfg, of, nullptr, 0, nullptr, out, of);
+}
+
 int eep_destroy(eep_ctx* ctx) {
   if (!ctx) return EEP_OK;
   eep_membership* m = ctx->mem;
   const bool is_root = m->members.front() == ctx;
   if (is_root && m->members.size() > 1) return EEP_ERR_STATE;  // attached contexts go first
+  if (ctx->n_staging > 0) return EEP_ERR_STATE;  // so do the staging sets that use its tables
   hipError_t e = hipDeviceSynchronize();
+  if (ctx->tables != ctx) ctx->tables->n_staging -= 1;
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   for (size_t i = 0; i < m->members.size(); ++i)
     if (m->members[i] == ctx) {
       m->members.erase(m->members.begin() + i);
@@ -279,7 +304,7 @@ int eep_set_membership(eep_ctx* c, const int32_t* active_host, void* stream) {
   // the mask is shared: every context of the instance that asked for strict
   // coverage must stay covered under its own placement
   for (eep_ctx* o : m->members)
-    if (o->cfg.strict_coverage &&
+    if (o->tables == o && o->cfg.strict_coverage &&
         host_uncovered_experts(o->P, o->E, o->S, o->h_p2l.data(), a.data()) > 0)
       return EEP_ERR_COVERAGE;
   hipError_t e = launch_patch(m->active, a.data(), c->R, m->mem_version, (hipStream_t)stream);
@@ -296,6 +321,7 @@ namespace eep {
 // unread detection round itself (eep_apply_repair looks the device mask up per transfer).
 int publish_placement(eep_ctx* c, const int32_t* p2l_host, bool mask_may_be_stale,
                       hipStream_t st) {
+  c = c->tables;  // a staging context names its owner's tables
   for (int p = 0; p < c->P; ++p)
     if (p2l_host[p] < -1 || p2l_host[p] >= c->E) return EEP_ERR_INVALID_ARG;
   if (c->cfg.strict_coverage) {
@@ -344,6 +370,31 @@ int eep_dispatch(eep_ctx* c, const void* x, const float* x_scale, void* recv_x, 
   if (!aligned16(x) || !aligned16(recv_x) || !aligned16(x_scale) || !aligned16(recv_scale))
     return EEP_ERR_ALIGN;
   hipError_t e = launch_pack(c, x, x_scale, recv_x, recv_scale, T, (hipStream_t)stream);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_staging_fork(eep_ctx* c, const int32_t* topk_idx, const void* x, const float* x_scale,
+                     void* recv_x, float* recv_scale, int32_t T, void* stream, void* side_stream) {
+  if (!c || !stream || !side_stream || stream == side_stream) return EEP_ERR_INVALID_ARG;
+  hipError_t e = hipSuccess;
+  if (!c->ev_fork) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess && !c->ev_join) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+  // the side stream starts after everything queued on `stream` so far
+  if (e == hipSuccess) e = hipEventRecord(c->ev_fork, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamWaitEvent((hipStream_t)side_stream, c->ev_fork, 0);
+  if (e != hipSuccess) return fail_hip(c, e);
+  int rc = eep_dispatch_layout(c, topk_idx, T, side_stream);
+  if (rc == EEP_OK) rc = eep_dispatch(c, x, x_scale, recv_x, recv_scale, T, side_stream);
+  // Whatever happened, the side stream is joined again by eep_staging_join; a stream left
+  // forked would make an enclosing capture fail.
+  return rc;
+}
+
+int eep_staging_join(eep_ctx* c, void* stream, void* side_stream) {
+  if (!c || !stream || !side_stream || stream == side_stream) return EEP_ERR_INVALID_ARG;
+  if (!c->ev_join) return EEP_ERR_STATE;  // no eep_staging_fork before
+  hipError_t e = hipEventRecord(c->ev_join, (hipStream_t)side_stream);
+  if (e == hipSuccess) e = hipStreamWaitEvent((hipStream_t)stream, c->ev_join, 0);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
 

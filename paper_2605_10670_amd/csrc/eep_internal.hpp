@@ -101,6 +101,12 @@ struct eep_ctx {
 
   // host shadows of the tables (coverage is validated without touching the GPU)
   std::vector<int32_t> h_p2l;
+  // Double-buffered staging: a staging context shares the placement tables (device arrays
+  // and host shadow) of `tables`, the context they belong to; an ordinary context points
+  // to itself.  n_staging counts the staging contexts that point here.
+  eep_ctx* tables;
+  int n_staging;
+  hipEvent_t ev_fork, ev_join;  // created on first use by eep_staging_fork
   int layout_T;  // T of the last dispatch_layout, -1 if none yet
   int last_hip_error;
   int64_t field_ints[EEP_V_NUM_FIELDS];

@@ -93,6 +93,7 @@ int eep_apply_repair(eep_ctx* c, void* weights, const void* backup, int64_t slot
     return EEP_ERR_INVALID_ARG;
   if (slot_bytes % 16 != 0 || ((uintptr_t)weights & 15u) || ((uintptr_t)backup & 15u))
     return EEP_ERR_ALIGN;
+  c = c->tables;  // a staging context names its owner's tables
   const int P = c->P, S = c->S;
   std::vector<int32_t> dst, src, expert;
   for (int p = 0; p < P; ++p) {
