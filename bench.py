@@ -440,6 +440,9 @@ def main():
                     help="also time dispatch alone and combine alone in loops of their own (out of "
                          "sequence: inside a step part of what dispatch writes is still draining "
                          "to HBM while combine runs, so the split between the two differs)")
+    ap.add_argument("--stage-only", choices=["dispatch", "combine"],
+                    help="for counter runs: after one whole step, launch only this stage --steps "
+                         "times (out of sequence) and print its mean time; nothing else is measured")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--calib", action="store_true",
                     help="first launch 5 plain copy kernels of 512 MiB (k_calibration_copy), the "
@@ -561,6 +564,15 @@ def main():
         ctx.signal_experts_done(stream)
     combine()
     stream.synchronize()
+    if args.stage_only:
+        fn = dispatch if args.stage_only == "dispatch" else combine
+        for _ in range(args.warmup):
+            fn()
+        us = time_events(stream, fn, args.steps) * 1e3
+        print(json.dumps({"workload": args.workload, "stage_only": args.stage_only,
+                          "steps": args.steps, "us_per_launch": us}))
+        ctx.destroy()
+        return
     dedup_info = None
     if dedup:           # one row per (token, rank): N_d rows are written instead of N
         n_d = ctx.read_dedup(T, stream)["N_d"]
