@@ -189,6 +189,8 @@ def cpu_baseline(wl, bytes_total, quant=False, budget_s=12.0):
 
 
 WORKLOADS = {
+    "tiny": ("tiny CPU-checkable step: T=128, H=1024 fp32, E=16, top-2, R=4 x (4+2) slots, rank 2 failed "
+             "and remapped, per-expert scalar stand-in (launch-latency-bound)"),
     "decode": ("dsv3-decode: T=4096 (32 ranks x 128), H=7168 bf16, E=256, top-8, 8+1 slots/rank, "
                "all live, identity expert"),
     "decode_failed_zipf": ("dsv3-decode, rank 13 failed and remapped to redundant slots, "
@@ -494,6 +496,8 @@ def main():
         wl = synth.decode_failed_zipf()
     elif args.workload == "prefill_fp8":
         wl = synth.prefill_fp8()
+    elif args.workload == "tiny":
+        wl = synth.tiny("c")
     else:
         wl = synth.churn_inputs(1)[0]
         wl.stub = "identity"
@@ -559,7 +563,9 @@ def main():
     if dedup:           # expansion on the destination, once, untimed: y = expert-major rows
         ctx.expand(recv, y, T, stream)
     elif wl.stub != "identity":
-        ctx.expert_stub(wl.stub, recv, y, T, recv_scale=recv_scale, stream=stream)
+        ctx.expert_stub(wl.stub, recv, y, T, recv_scale=recv_scale,
+                        expert_scale=dev(wl.expert_scale) if wl.expert_scale is not None else None,
+                        stream=stream)
     elif args.detect:
         ctx.signal_experts_done(stream)
     combine()
