@@ -187,6 +187,32 @@ def test_wide_and_odd_shapes(oracle, shape):
     assert got["N"] == T * k
 
 
+@pytest.mark.parametrize("R,T,H,k", [
+    (32, 8192, 512, 4),      # 1 vector per lane: 4 tokens per wavefront (2048 wavefronts)
+    (32, 8192, 2560, 3),     # 5 per lane: 4 tokens per wavefront
+    (32, 8192, 6656, 2),     # 13 per lane: 4 x 13 = 52 vectors per lane, the widest multi-token form
+    (32, 12288, 3584, 2),    # 7 per lane, T = 3 * 4096: 4 tokens per wavefront (8 would leave 1536 wavefronts)
+    (32, 16384, 1536, 2),    # 3 per lane: 8 tokens per wavefront
+    (6, 8190, 1024, 4),      # T is even but not a multiple of 4: 2 tokens per wavefront
+])
+def test_pack_with_several_tokens_per_wavefront(oracle, R, T, H, k):
+    """Batches of 8192 tokens and more take the pack form in which a wavefront moves 2, 4 or 8
+    tokens; every combination of pass width and token count used here goes through the
+    whole step and is compared with the oracle."""
+    rng = np.random.default_rng(T + H + k)
+    sp, sr = 2, 1
+    E = R * sp
+    x = synth.f32_to_bf16_bits(rng.standard_normal((T, H), dtype=np.float32))
+    idx, w = synth.router_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    pref = synth.preferred_placement(R, sp, sr)
+    failed = (R // 3,)
+    p2l = synth.repaired_placement(pref, failed, R, sp, sr)
+    wl = synth.Workload("multi", T, H, E, k, R, sp, sr, "bf16", "bf16", "bf16", "identity", failed,
+                        idx, w, x, p2l, synth.active_mask(R, failed))
+    got, _ = run_and_compare(oracle, wl)
+    assert got["N"] == T * k and got["rank_count"][failed[0]] == 0
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configurations(oracle, seed):
     """Seeded random instances: rank/slot/expert counts, top-k, token counts that
