@@ -272,14 +272,19 @@ int eep_expert_stub(eep_ctx* ctx, int32_t kind, const void* recv_x, const float*
  * One-GPU emulation of the paper's signal counters.  Every eep_dispatch_layout
  * advances a device-side step epoch.  The expert stage announces "the outputs of
  * rank r for this step are there" by storing the epoch into rank r's signal word
- * (release); eep_combine, when detection is on, first waits -- inside a kernel,
- * for at most the timeout -- until every ACTIVE rank's signal shows the epoch.
- * A rank that stays silent is dropped by that kernel: its active bit is cleared
- * in the device table, its failure is recorded, and the pairs routed to it
- * contribute nothing to this step's outputs (the paper fails such in-flight
- * requests, Sec. 3.1).  Later steps, replayed graphs included, route around the
- * rank with no host action; the host finds out with eep_read_failures, then
- * repairs the placement (eep_plan_repair, eep_update_placement).
+ * (release).  With detection on, the combine kernel itself polls those words:
+ * before a wavefront reduces a token's rows it looks at the signal of every rank
+ * the rows come from, and waits -- for at most the timeout -- for a word that
+ * does not show the epoch yet.  Ranks from which the step expects nothing are
+ * not awaited.  A rank that stays silent is dropped by the kernel: its active
+ * entry is cleared in the device table, the membership version is bumped, its
+ * failure is recorded, and the pairs routed to it contribute nothing to this
+ * step's outputs and lose their row_of entry (the paper fails such in-flight
+ * requests, Sec. 3.1).  Waiting wavefronts notice a drop made by another one, so
+ * a step with a silent rank takes about one timeout longer, not more.  Later
+ * steps, replayed graphs included, route around the rank with no host action;
+ * the host finds out with eep_read_failures, then repairs the placement
+ * (eep_plan_repair, eep_update_placement).
  * Switching detection on or off changes which kernels eep_combine and
  * eep_expert_stub launch, so choose before capturing a graph. */
 

@@ -357,19 +357,25 @@ void eeo_stub_dequant(int N, int H, int group, const uint8_t* q, const float* sc
  * One round of waiting, seen from the combine side of a step whose routing
  * (slot_of, row_of) was made under the mask active[R]:
  *   arrived[r] != 0  rank r's signal for this round came within the time-out.
- * Only ACTIVE peers are awaited.  An active rank whose signal did not arrive is
- * deemed failed: its active entry is cleared (later steps route around it), it
- * is put on the failure report that the host reads after the step, and the
- * pairs routed to it in this step contribute nothing (their requests are
- * failed, Sec. 3.1): their row_of entry becomes -1 so that the combine skips
- * them.  Arrays are updated in place; report[R] is written (1 = dropped now).
- * Returns the number of pairs withdrawn. */
+ * A side waits for the arrivals it EXPECTS from the active peer set (Sec. 3.4):
+ * the ranks that hold rows of this step.  A rank that is not active, or from
+ * which nothing is expected in this round, is not awaited.  An awaited rank
+ * whose signal did not arrive is deemed failed: its active entry is cleared
+ * (later steps route around it), it is put on the failure report that the host
+ * reads after the step, and the pairs routed to it in this step contribute
+ * nothing (their requests are failed, Sec. 3.1): their row_of entry becomes -1
+ * so that the combine skips them.  Arrays are updated in place; report[R] is
+ * written (1 = dropped now).  Returns the number of pairs withdrawn. */
 int64_t eeo_detect_round(int T, int k, int R, int S, const int32_t* slot_of,
                          const int32_t* arrived, int32_t* active, int32_t* report,
                          int32_t* row_of) {
   for (int r = 0; r < R; ++r) {
     report[r] = 0;
     if (active[r] == 0) continue; /* not awaited */
+    int expected = 0;             /* rows of this step that rank r holds */
+    for (int i = 0; i < T * k; ++i)
+      if (slot_of[i] >= 0 && row_of[i] >= 0 && slot_of[i] / S == r) ++expected;
+    if (expected == 0) continue;  /* nothing to wait for in this round */
     if (arrived[r] != 0) continue;
     active[r] = 0;
     report[r] = 1;

@@ -120,7 +120,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   int64_t total = 0;
   for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) total += round_up(n[i] > 0 ? n[i] : 1);
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
-  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 3 * round_up(1) +
+  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 4 * round_up(1) +
            3 * round_up(c->R) + 4 * round_up(c->P);
   const int64_t n_dd_tile = (int64_t)c->max_tiles * c->R;
   total += 3 * round_up(pairs > 0 ? pairs : 1) + round_up(c->R) + round_up(c->R + 1) +
@@ -167,6 +167,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   c->tbl_version = cur; cur += round_up(1);
   c->mem_version_word = cur; cur += round_up(1);
   c->step_epoch = cur;  cur += round_up(1);
+  c->round_ok = cur;    cur += round_up(1);
   c->signal = cur;      cur += round_up(c->R);
   c->withhold = cur;    cur += round_up(c->R);
   c->report = cur;      cur += round_up(c->R);
@@ -422,12 +423,9 @@ int eep_combine(eep_ctx* c, const void* y, const float* topk_w, void* out, int32
   if (T == 0) return EEP_OK;
   if (!y || !topk_w || !out) return EEP_ERR_INVALID_ARG;
   if (!aligned16(y) || !aligned16(out)) return EEP_ERR_ALIGN;
-  hipError_t e = hipSuccess;
-  if (c->detect_timeout_ticks > 0) {
-    e = launch_await(c, T, (hipStream_t)stream);
-    c->mem->unread_round = true;  // until eep_read_failures has looked at the report
-  }
-  if (e == hipSuccess) e = launch_combine(c, y, topk_w, out, T, (hipStream_t)stream);
+  // with detection on, the kernel itself waits for the ranks' signals and may drop one
+  if (c->detect_timeout_ticks > 0) c->mem->unread_round = true;  // until eep_read_failures
+  hipError_t e = launch_combine(c, y, topk_w, out, T, (hipStream_t)stream);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
 

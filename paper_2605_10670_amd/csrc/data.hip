@@ -475,18 +475,108 @@ __device__ inline void store_out(void* out_row, int v, const float (&acc)[YVec<Y
   }
 }
 
+// ---------------------------------------------------------------------------
+// GPU-side failure detection inside combine (paper Sec. 3.4; Sec. 4.1, the
+// paragraph on failure detection from the GPU side): before a wavefront reduces
+// a token's rows it looks at the signal word of every rank those rows come
+// from.  The expert stage stores the step's epoch there once the rank's outputs
+// are in place.  A word that does not show the epoch sends the wavefront into
+// the wait below; a rank that stays silent past the time-out is dropped by the
+// kernel: its `active` entry is cleared, it is put on the report that the host
+// reads after the kernel, the membership version is bumped, and the pairs
+// routed to it contribute nothing (their row_of entry becomes -1).
+// In a healthy step the first wavefront of the launch finds every expected
+// signal in place and publishes that in one word (round_ok = epoch); the others
+// read that word (one agent-scope load, issued beside the row loads) and go
+// straight on.  Wavefronts that run before the word is published, and all
+// wavefronts of a step in which a signal is missing, look at the signals of
+// their own rows' ranks.  Those first looks use plain loads: the signal words
+// were written by an earlier launch of the same stream.  The wait itself uses agent-scope loads,
+// so that a rank dropped by a wavefront on another XCD is seen at once and all
+// waiting wavefronts together spend about one time-out, not one each.  Every
+// wait is bounded by the wall clock and by a poll count.
+// ---------------------------------------------------------------------------
+struct DetectArgs {
+  const int32_t* slot_of;     // [T, k]
+  int32_t* row_of;            // [T, k], entries of dropped pairs are set to -1
+  const int32_t* signal;      // [R] epoch of the last step whose outputs arrived
+  const int32_t* step_epoch;  // current step
+  int32_t* active;            // [R]
+  int32_t* report;            // [R]
+  int32_t* mem_version;
+  const int32_t* rank_count;  // [R] rows each rank holds in this step
+  int32_t* round_ok;          // epoch of the last step in which every expected signal was there
+  int R, S;
+  long long timeout_ticks, max_polls;
+};
+
+// pending: bit j set = pair j's rank has not signalled.  Returns the bits of the pairs whose
+// rank was dropped (by this wavefront or by another).  Uniform across the wavefront.
+__device__ __forceinline__ uint32_t await_late_ranks(const DetectArgs& d, int64_t pair0, uint32_t pending,
+                                                  int epoch) {
+  uint32_t failed = 0;
+  const long long t0 = wall_clock64();
+  long long polls = 0;
+  while (pending != 0) {
+    for (uint32_t m = pending; m != 0; m &= m - 1) {
+      const int j = __ffs(m) - 1;
+      const int rank = d.slot_of[pair0 + j] / d.S;
+      if (__hip_atomic_load(&d.signal[rank], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == epoch) {
+        pending &= ~(1u << j);  // arrived late
+      } else if (__hip_atomic_load(&d.active[rank], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+        pending &= ~(1u << j);  // dropped meanwhile
+        failed |= 1u << j;
+      }
+    }
+    if (pending == 0) break;
+    if (++polls > d.max_polls || wall_clock64() - t0 > d.timeout_ticks) {
+      // time-out: drop every rank still awaited; the first wavefront to clear the entry
+      // also reports it
+      for (uint32_t m = pending; m != 0; m &= m - 1) {
+        const int j = __ffs(m) - 1;
+        const int rank = d.slot_of[pair0 + j] / d.S;
+        if (threadIdx.x == 0 &&
+            __hip_atomic_exchange(&d.active[rank], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+          __hip_atomic_store(&d.report[rank], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_add(d.mem_version, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        failed |= 1u << j;
+      }
+      break;
+    }
+    __builtin_amdgcn_s_sleep(8);
+  }
+  if (threadIdx.x == 0)
+    for (uint32_t m = failed; m != 0; m &= m - 1) d.row_of[pair0 + __ffs(m) - 1] = -1;
+  return failed;
+}
+
+// First look (plain loads) at the signals of the ranks a token's rows come from; the wait only
+// if one is missing.  Returns the bits of the pairs whose rank was dropped.
+__device__ __forceinline__ uint32_t ranks_dropped(const DetectArgs& d, int64_t pair0, int k,
+                                                  const int32_t* rows, int epoch) {
+  uint32_t pending = 0;
+  for (int j = 0; j < k; ++j) {
+    const int p = d.slot_of[pair0 + j];
+    if (p >= 0 && rows[j] >= 0 && d.signal[p / d.S] != epoch) pending |= 1u << j;
+  }
+  return pending != 0 ? await_late_ranks(d, pair0, pending, epoch) : 0u;
+}
+
 // One wavefront per (token, part): a part is kCombineCols * 64 16-byte columns
 // of the row (2 KiB of each source row at the decode shape), so a lane has
 // kCombineCols * k independent loads in flight.  Small single-wavefront
 // workgroups measured ~10 % faster than one workgroup per token.
 constexpr int kCombineCols = 2;
 
-template <bool Y_BF16, bool OUT_BF16, int K>
+// DETECT: the wait for the ranks' signals is part of the kernel (DetectArgs above); row_of
+// is then not read-only, because dropped pairs are struck from it.
+template <bool Y_BF16, bool OUT_BF16, int K, bool DETECT>
 __global__ __launch_bounds__(64) void k_combine(const u32x4* __restrict__ y,
                                                 const float* __restrict__ topk_w,
-                                                const int32_t* __restrict__ row_of,
-                                                void* __restrict__ out, int k, int row_vecs,
-                                                int parts, int64_t out_row_bytes) {
+                                                const int32_t* row_of, void* __restrict__ out,
+                                                int k, int row_vecs, int parts,
+                                                int64_t out_row_bytes, DetectArgs det) {
   constexpr int NE = YVec<Y_BF16>::kElems;
   const int t = blockIdx.x / parts;
   const int part = blockIdx.x - t * parts;
@@ -494,6 +584,20 @@ __global__ __launch_bounds__(64) void k_combine(const u32x4* __restrict__ y,
   const int32_t* rows = row_of + (int64_t)t * k;
   const float* ws = topk_w + (int64_t)t * k;
   void* out_row = (char*)out + (int64_t)t * out_row_bytes;
+
+  int round_flag = 0, epoch = 0;
+  if constexpr (DETECT) {
+    epoch = *det.step_epoch;
+    if (blockIdx.x == 0) {
+      // the first wavefront looks at every rank that holds rows of this step
+      bool ok = true;
+      for (int r = threadIdx.x; r < det.R; r += 64)
+        ok &= det.active[r] == 0 || det.rank_count[r] == 0 || det.signal[r] == epoch;
+      if (__all(ok) && threadIdx.x == 0)
+        __hip_atomic_store(det.round_ok, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    round_flag = __hip_atomic_load(det.round_ok, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
 
   if constexpr (K > 0) {
     // fast path: compile-time k and every pair routed -> no branch between loads
@@ -517,6 +621,12 @@ __global__ __launch_bounds__(64) void k_combine(const u32x4* __restrict__ y,
             d[q][j] = __builtin_nontemporal_load(&y[(int64_t)r[j] * row_vecs + v]);
         }
       }
+      // the look at the ranks' signals comes after the row loads have been issued, so that
+      // its two dependent table lookups overlap with them; rows of a rank that turns out to
+      // be dropped are loaded and not used
+      uint32_t dropped = 0;
+      if constexpr (DETECT)
+        if (round_flag != epoch) dropped = ranks_dropped(det, (int64_t)t * k, k, rows, epoch);
 #pragma unroll
       for (int q = 0; q < kCombineCols; ++q) {
         int v = v0 + q * 64;
@@ -525,13 +635,17 @@ __global__ __launch_bounds__(64) void k_combine(const u32x4* __restrict__ y,
 #pragma unroll
           for (int i = 0; i < NE; ++i) acc[i] = 0.0f;
 #pragma unroll
-          for (int j = 0; j < K; ++j) accumulate<Y_BF16>(acc, d[q][j], w[j]);
+          for (int j = 0; j < K; ++j)
+            if (!DETECT || !((dropped >> j) & 1u)) accumulate<Y_BF16>(acc, d[q][j], w[j]);
           store_out<Y_BF16, OUT_BF16>(out_row, v, acc);
         }
       }
       return;
     }
   }
+  uint32_t dropped = 0;  // bit j: pair j's rank was dropped in this step
+  if constexpr (DETECT)
+    if (round_flag != epoch) dropped = ranks_dropped(det, (int64_t)t * k, k, rows, epoch);
   for (int q = 0; q < kCombineCols; ++q) {
     int v = v0 + q * 64;
     if (v >= row_vecs) break;
@@ -540,7 +654,7 @@ __global__ __launch_bounds__(64) void k_combine(const u32x4* __restrict__ y,
     for (int i = 0; i < NE; ++i) acc[i] = 0.0f;
     for (int j = 0; j < k; ++j) {
       int row = rows[j];
-      if (row < 0) continue;
+      if (row < 0 || ((dropped >> j) & 1u)) continue;
       u32x4 d = __builtin_nontemporal_load(&y[(int64_t)row * row_vecs + v]);
       accumulate<Y_BF16>(acc, d, ws[j]);
     }
@@ -555,12 +669,33 @@ static hipError_t launch_combine_t(eep_ctx* c, const void* y, const float* w, vo
   int parts = (row_vecs + 64 * kCombineCols - 1) / (64 * kCombineCols);
   if ((int64_t)T * parts > 0x7fffffffLL) return hipErrorInvalidValue;  // grid size limit
   dim3 grid((unsigned)((int64_t)T * parts)), block(64);
+  DetectArgs det = {};
+  if (c->detect_timeout_ticks > 0) {
+    // the wait for the ranks' signals runs inside the kernel
+    det.slot_of = c->slot_of; det.row_of = c->row_of; det.signal = c->signal;
+    det.step_epoch = c->step_epoch; det.active = c->active; det.report = c->report;
+    det.mem_version = c->mem->mem_version; det.S = c->S; det.R = c->R;
+    det.rank_count = c->rank_count; det.round_ok = c->round_ok;
+    det.timeout_ticks = c->detect_timeout_ticks;
+    det.max_polls = c->detect_timeout_ticks * 8 + 1024;
+    if (c->k == 8)
+      hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 8, true>), grid, block, 0, st,
+                         (const u32x4*)y, w, c->row_of, out, c->k, row_vecs, parts,
+                         c->out_row_bytes, det);
+    else
+      hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 0, true>), grid, block, 0, st,
+                         (const u32x4*)y, w, c->row_of, out, c->k, row_vecs, parts,
+                         c->out_row_bytes, det);
+    return hipGetLastError();
+  }
   if (c->k == 8)
-    hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 8>), grid, block, 0, st, (const u32x4*)y, w,
-                       c->row_of, out, c->k, row_vecs, parts, c->out_row_bytes);
+    hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 8, false>), grid, block, 0, st,
+                       (const u32x4*)y, w, c->row_of, out, c->k, row_vecs, parts,
+                       c->out_row_bytes, det);
   else
-    hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 0>), grid, block, 0, st, (const u32x4*)y, w,
-                       c->row_of, out, c->k, row_vecs, parts, c->out_row_bytes);
+    hipLaunchKernelGGL((k_combine<Y_BF16, OUT_BF16, 0, false>), grid, block, 0, st,
+                       (const u32x4*)y, w, c->row_of, out, c->k, row_vecs, parts,
+                       c->out_row_bytes, det);
   return hipGetLastError();
 }
 

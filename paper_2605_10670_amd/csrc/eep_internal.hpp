@@ -87,6 +87,7 @@ struct eep_ctx {
   // epoch of the last step whose expert outputs arrived), test knob that mutes
   // a rank, failure report written by the waiting kernel
   int32_t *step_epoch, *signal, *withhold, *report;
+  int32_t* round_ok;  // epoch of the last step whose combine found every expected signal in place
   // repair batch: destination slot, source slot (-1 = backup), logical expert of
   // each move, and what the relocation kernel did per slot
   int32_t *mv_dst, *mv_src, *mv_expert, *mv_outcome;
@@ -149,7 +150,6 @@ hipError_t launch_stub(eep_ctx* c, int kind, const void* recv_x, const float* re
                        const float* expert_scale, void* y, int T, hipStream_t st);
 // detect.hip
 hipError_t launch_signal(eep_ctx* c, hipStream_t st);
-hipError_t launch_await(eep_ctx* c, int T, hipStream_t st);
 // api.hip
 int publish_placement(eep_ctx* c, const int32_t* p2l_host, bool mask_may_be_stale, hipStream_t st);
 // tables.hip

@@ -56,6 +56,24 @@ def test_only_active_peers_are_awaited_and_a_full_round_changes_nothing(oracle):
     assert det["withdrawn"] == lay["N"]
 
 
+def test_a_rank_from_which_nothing_is_expected_is_not_awaited(oracle):
+    """Sec. 3.4: a side waits for the EXPECTED arrivals from the active peer set.  Here no
+    token routes to rank 3 in this step, so its silence goes unnoticed (and is noticed in the
+    first round in which it holds rows)."""
+    R, S, k, T, H = 4, 2, 2, 8, 4
+    E = R * S
+    idx = np.tile(np.array([[0, 3]], np.int32), (T, 1))          # experts of ranks 0 and 1 only
+    silent = np.array([1, 1, 1, 0], np.int32)
+    lay = oracle.step_layout(idx, np.arange(E, dtype=np.int32), np.ones(R, np.int32), E, R, S, S, 0)
+    assert lay["rank_count"].tolist() == [T, T, 0, 0]
+    det = oracle.detect_round(lay["slot_of"], lay["row_of"], np.ones(R, np.int32), silent, S)
+    assert det["report"].sum() == 0 and det["active"].tolist() == [1, 1, 1, 1]
+    idx2 = np.tile(np.array([[0, 6]], np.int32), (T, 1))         # now rank 3 holds rows
+    lay = oracle.step_layout(idx2, np.arange(E, dtype=np.int32), np.ones(R, np.int32), E, R, S, S, 0)
+    det = oracle.detect_round(lay["slot_of"], lay["row_of"], np.ones(R, np.int32), silent, S)
+    assert det["report"].tolist() == [0, 0, 0, 1] and det["withdrawn"] == T
+
+
 @pytest.mark.parametrize("policy", [0, 1])
 def test_replicated_placement_invariants(oracle, policy):
     """Decode-like tables with replicas: the rows withdrawn are exactly the dropped ranks'
