@@ -35,13 +35,13 @@ STAGE_KERNELS = {"dispatch": ("k_pack", "k_pack_multi", "k_pack_quant", "k_scale
 
 
 def source_hash():
-    """Hash of the HIP sources the library is built from (the built .so travels with them)."""
-    import glob
+    """Hash of the HIP sources that hold every kernel of the step (layout.hip, data.hip); the
+    built .so travels with them."""
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2605_10670_amd", "csrc", "*"))):
-        h.update(os.path.basename(f).encode())
-        h.update(open(f, "rb").read())
+    for name in ("data.hip", "layout.hip"):
+        h.update(name.encode())
+        h.update(open(os.path.join(ROOT, "paper_2605_10670_amd", "csrc", name), "rb").read())
     return h.hexdigest()[:16]
 
 
