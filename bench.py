@@ -676,7 +676,7 @@ def main():
         # that sits between two calls, estimated in the same run as (sum of the three stage
         # times - time of an eager step without inner events) / 3; agrees with rocprofv3's
         # kernel durations to within 0.5 % (profiles/).  With an fp8 payload the dispatch
-        # stage is k_pack plus the small k_pack_scales launch.
+        # stage is the payload kernel plus the small k_scale_rows launch.
         launch_ms = stage_ms[stage] - event_cost_ms
         gbs = nbytes[stage] / (launch_ms * 1e-3) / 1e9
         kernels[kname] = {"avg_launch_us": launch_ms * 1e3,
