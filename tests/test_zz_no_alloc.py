@@ -99,6 +99,58 @@ def test_noalloc_layout_tiny_other_topk(oracle):
     assert got["rank_count"][2] == 0
 
 
+def test_noalloc_layout_of_an_empty_batch():
+    R, S, E, k = 4, 3, 8, 2
+    out = _device_outputs(8, k, R, R * S, fill=-7)
+    binding.dispatch_layout_noalloc(R=R, S=S, E=E, k=k, policy=0, topk_idx=None, out=out, T=0,
+                                    active=torch.ones(R, dtype=torch.int32, device="cuda"),
+                                    l2p_off=torch.zeros(E + 1, dtype=torch.int32, device="cuda"),
+                                    l2p_list=torch.zeros(R * S, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    got, tail = _host(out, 0, k, R, R * S)
+    assert got["N"] == 0 and got["n_uncovered"] == 0 and got["n_masked"] == 0
+    assert not got["count"].any() and not got["offset"].any() and not got["cnt_src"].any()
+    assert not got["rank_count"].any() and not got["rank_offset"].any()
+    assert all((a == -7).all() for a in tail.values())        # no pair, nothing per pair written
+
+
+def test_noalloc_layout_inside_a_captured_graph(oracle):
+    """What the entry point is for: a caller under stream capture.  Captured once, replayed
+    with new router outputs and a new mask in the same device buffers, with eager work in
+    between; every replay is compared with the oracle."""
+    T = 2048
+    wls = [_workload(T, (), 60), _workload(T, (11,), 61), _workload(T, (11, 30), 62)]
+    wl = wls[0]
+    R, S, P, E, k = wl.R, wl.S, wl.P, wl.E, wl.k
+    out = _device_outputs(T, k, R, P, fill=-7)
+    idx = gu.to_dev(wl.topk_idx)
+    off, lst = binding.host_replica_lists(wl.p2l, E, S, wl.S_prim)
+    active, l2p_off, l2p_list = gu.to_dev(wl.active), gu.to_dev(off), gu.to_dev(lst)
+    stream = torch.cuda.Stream()
+    call = lambda: binding.dispatch_layout_noalloc(
+        R=R, S=S, E=E, k=k, policy=binding.SPREAD, topk_idx=idx, active=active, l2p_off=l2p_off,
+        l2p_list=l2p_list, out=out, T=T, stream=stream)
+    call()                               # eager once: the scratch address is resolved here
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call()
+    for step in range(5):
+        w = wls[step % 3]
+        off, lst = binding.host_replica_lists(w.p2l, E, S, w.S_prim)
+        idx.copy_(gu.to_dev(w.topk_idx))                 # eager work between the replays
+        active.copy_(gu.to_dev(w.active))
+        l2p_off.copy_(gu.to_dev(off))
+        l2p_list.copy_(gu.to_dev(lst))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got, _ = _host(out, T, k, R, P)
+        ref = oracle.step_layout(w.topk_idx, w.p2l, w.active, E, R, S, w.S_prim, oracle.SPREAD)
+        gu.assert_layout_equal(got, ref, T, k)
+        assert not got["rank_count"][w.active == 0].any()
+
+
 def test_noalloc_layout_refuses_what_does_not_fit():
     R, S, E, k = 32, 9, 256, 8
     out = _device_outputs(64, k, R, R * S, fill=0)
