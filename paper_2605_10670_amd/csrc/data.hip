@@ -240,6 +240,7 @@ static hipError_t launch_pack_any(eep_ctx* c, const int32_t* rows, const void* x
   if (e != hipSuccess || x_scale == nullptr) return e;
   const int scale_vecs = (int)(c->scale_row_bytes / 16);
   const int64_t vecs = (int64_t)T * c->k * scale_vecs;
+  if ((vecs + kScaleThreads - 1) / kScaleThreads > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_scale_rows, dim3((unsigned)((vecs + kScaleThreads - 1) / kScaleThreads)),
                      dim3(kScaleThreads), 0, st, (const u32x4*)x_scale, (u32x4*)recv_scale,
                      c->src_of, c->status, c->k, scale_vecs);
