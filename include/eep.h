@@ -340,6 +340,20 @@ typedef enum {
  * array into host memory.  n beyond the array's allocated size is an error. */
 int eep_read_view(eep_ctx* ctx, int32_t field, int32_t* host_dst, int64_t n, void* stream);
 
+/* Debug helper: the bounds assertion of the path as a call.  eep_dispatch and
+ * eep_combine index the caller's buffers with row_of without further checks;
+ * this checks, on the device, the layout that the last eep_dispatch_layout of
+ * the same T left behind, waits for `stream` and returns four counts (all zero
+ * for a sound layout):
+ *   [0] pairs whose row lies outside its slot's rows [offset[p], offset[p+1]),
+ *       or outside [0, N), or whose slot is outside [-1, P)
+ *   [1] pairs whose row's src_of entry is not the pair
+ *   [2] rows below N whose src_of is out of range or does not point at a pair
+ *       holding the row; rows from N on whose src_of is not -1
+ *   [3] routed pairs without a row: not a violation by itself, it is what
+ *       failure detection leaves behind when it drops a rank within the step */
+int eep_debug_check_layout(eep_ctx* ctx, int32_t T, int32_t violations_host[4], void* stream);
+
 /* Measurement helper: a plain copy kernel (dst[i] = src[i], 16-byte vectors,
  * bytes a multiple of 16, both device pointers 16-byte aligned).  It moves
  * exactly `bytes` in and `bytes` out, which makes it the yardstick that

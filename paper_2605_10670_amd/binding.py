@@ -89,6 +89,7 @@ def load():
         "eep_dispatch_quant": [vp, vp, vp, vp, i32, vp],
         "eep_combine": [vp, vp, vp, vp, i32, vp],
         "eep_expert_stub": [vp, i32, vp, vp, vp, vp, i32, vp],
+        "eep_debug_check_layout": [vp, i32, vp, vp],
         "eep_get_view": [vp, ctypes.POINTER(_View)],
         "eep_read_view": [vp, i32, vp, i64, vp],
         "eep_last_hip_error": [vp],
@@ -429,6 +430,13 @@ class Context:
         out = np.empty(n, np.int32)
         _check(load().eep_read_view(self._h, VIEW_FIELDS.index(field), out.ctypes.data, n,
                                     _stream(stream)), "eep_read_view", self._h)
+        return out
+
+    def check_layout(self, T, stream=None):
+        """eep_debug_check_layout -> int32[4] violation counts (see eep.h)."""
+        out = np.zeros(4, np.int32)
+        _check(load().eep_debug_check_layout(self._h, T, out.ctypes.data, _stream(stream)),
+               "eep_debug_check_layout", self._h)
         return out
 
     def read_layout(self, T, stream=None):

@@ -120,7 +120,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   int64_t total = 0;
   for (int i = 0; i < EEP_V_NUM_FIELDS; ++i) total += round_up(n[i] > 0 ? n[i] : 1);
   const int64_t n_tile = (int64_t)c->max_tiles * c->P;
-  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 4 * round_up(1) +
+  total += 2 * round_up(n_tile) + 2 * round_up(c->max_tiles) + 5 * round_up(1) +
            3 * round_up(c->R) + 4 * round_up(c->P);
   const int64_t n_dd_tile = (int64_t)c->max_tiles * c->R;
   total += 3 * round_up(pairs > 0 ? pairs : 1) + round_up(c->R) + round_up(c->R + 1) +
@@ -168,6 +168,7 @@ int create_impl(const eep_config* cfg, eep_ctx* parent, void* workspace, int64_t
   c->mem_version_word = cur; cur += round_up(1);
   c->step_epoch = cur;  cur += round_up(1);
   c->round_ok = cur;    cur += round_up(1);
+  c->check_bad = cur;   cur += round_up(1);
   c->signal = cur;      cur += round_up(c->R);
   c->withhold = cur;    cur += round_up(c->R);
   c->report = cur;      cur += round_up(c->R);
@@ -559,6 +560,17 @@ int eep_read_dedup(eep_ctx* c, int32_t field, int32_t* host_dst, int64_t n, void
   hipError_t e = hipStreamSynchronize((hipStream_t)stream);
   if (e == hipSuccess)
     e = hipMemcpy(host_dst, src[field], (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost);
+  return e == hipSuccess ? EEP_OK : fail_hip(c, e);
+}
+
+int eep_debug_check_layout(eep_ctx* c, int32_t T, int32_t violations_host[4], void* stream) {
+  if (!c || !violations_host || T < 0 || T > c->T_max) return EEP_ERR_INVALID_ARG;
+  if (c->layout_T != T) return EEP_ERR_STATE;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_check_layout(c, T, c->check_bad, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e == hipSuccess)
+    e = hipMemcpy(violations_host, c->check_bad, 4 * sizeof(int32_t), hipMemcpyDeviceToHost);
   return e == hipSuccess ? EEP_OK : fail_hip(c, e);
 }
 

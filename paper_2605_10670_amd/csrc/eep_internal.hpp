@@ -88,6 +88,7 @@ struct eep_ctx {
   // a rank, failure report written by the waiting kernel
   int32_t *step_epoch, *signal, *withhold, *report;
   int32_t* round_ok;  // epoch of the last step whose combine found every expected signal in place
+  int32_t* check_bad;  // [4] violation counters of eep_debug_check_layout
   // repair batch: destination slot, source slot (-1 = backup), logical expert of
   // each move, and what the relocation kernel did per slot
   int32_t *mv_dst, *mv_src, *mv_expert, *mv_outcome;
@@ -134,6 +135,7 @@ struct LayoutIO {
 bool layout_shape_fits(int E, int P, int R, int k);  // tables fit the kernels' LDS budget
 hipError_t launch_layout(const LayoutIO& io, int T, hipStream_t st);
 hipError_t launch_layout(eep_ctx* c, const int32_t* topk_idx, int T, hipStream_t st);
+hipError_t launch_check_layout(eep_ctx* c, int T, int32_t* bad /* device [4] */, hipStream_t st);
 // data.hip
 hipError_t launch_pack(eep_ctx* c, const void* x, const float* x_scale, void* recv_x,
                        float* recv_scale, int T, hipStream_t st);

@@ -78,6 +78,7 @@ def test_silent_rank_is_dropped_by_the_kernel(oracle, use_graph, T_batch):
         assert np.array_equal(got["row_of"], det["row_of"])        # its pairs lost their row
         assert np.array_equal(out, chain)
         assert det["withdrawn"] == lay["rank_count"][SILENT] > 0
+        assert ctx.check_layout(T, stream).tolist() == [0, 0, 0, det["withdrawn"]]
         assert det["active"].tolist() == dead.tolist()
         assert ctx.read("active", R, stream).tolist() == dead.tolist()   # cleared by the kernel
         assert got["version"] == version       # this step's layout ran before the drop

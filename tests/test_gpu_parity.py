@@ -43,6 +43,7 @@ def run_and_compare(oracle, wl, policy=binding.SPREAD, strict=True):
         ref = oracle_step(oracle, wl, policy)
         got = ctx.read_layout(wl.T)
         gu.assert_layout_equal(got, ref["lay"], wl.T, wl.k)
+        assert ctx.check_layout(wl.T).tolist() == [0, 0, 0, 0]      # the device-side bounds check
         N = got["N"]
         recv = gu.to_host(dev.recv, gu.NP_OF[wl.x_dtype])
         assert np.array_equal(recv[:N].view(np.uint8), ref["recv"][:N].view(np.uint8)), "packed rows"
@@ -553,6 +554,55 @@ def test_special_values_follow_ieee(oracle, dtypes):
         got_bits = out.view(np.uint32) if od == "f32" else out
         assert np.array_equal(got_bits[~want_nan], want_bits[~want_nan])
         assert np.isinf(chain).any() and (np.abs(chain[np.isfinite(chain)]) < 1e-37).any()
+    finally:
+        ctx.destroy()
+
+
+def test_device_side_layout_check_sees_planted_errors():
+    """eep_debug_check_layout on a sound layout and on layouts whose arrays were overwritten
+    from the host (the check itself never indexes with an unchecked value)."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    wl = synth.decode(T=512, H=256)
+    ctx = gu.make_context(wl)
+    try:
+        gu.apply_tables(ctx, wl.p2l, wl.active)
+        idx = gu.to_dev(wl.topk_idx)
+        ctx.dispatch_layout(idx, wl.T)
+        assert ctx.check_layout(wl.T).tolist() == [0, 0, 0, 0]
+        lay = ctx.read_layout(wl.T)
+        ptr = ctx.view_pointers()
+
+        def poke(field, host):
+            host = np.ascontiguousarray(host, np.int32)
+            assert hip.hipMemcpy(ctypes.c_void_p(ptr[field]), host.ctypes.data_as(ctypes.c_void_p),
+                                 ctypes.c_size_t(host.nbytes), 1) == 0
+
+        rows = lay["row_of"].ravel().copy()
+        bad = rows.copy()
+        bad[5] = wl.T * wl.k + 17                  # beyond the buffer
+        bad[9] = -5                                # negative, not the marker
+        a, b = 100, 101                            # two pairs swap rows: each row is in range
+        bad[a], bad[b] = rows[b], rows[a]          # of the other's slot at best, and src_of
+        poke("row_of", bad)                        # no longer points back
+        got = ctx.check_layout(wl.T)
+        assert got[0] + got[1] >= 4 and got[3] == 0
+        poke("row_of", rows)
+        assert ctx.check_layout(wl.T).tolist() == [0, 0, 0, 0]
+        src = lay["src_of"].copy()
+        src[3] = wl.T * wl.k                       # out of range
+        src[7] = src[8]                            # a pair that holds another row
+        poke("src_of", src)
+        got = ctx.check_layout(wl.T)
+        assert got[2] == 2 and got[1] == 2 and got[0] == 0
+        poke("src_of", lay["src_of"])
+        withdrawn = rows.copy()
+        withdrawn[40:48] = -1                      # what a dropped rank leaves behind
+        poke("row_of", withdrawn)
+        assert ctx.check_layout(wl.T).tolist() == [0, 0, 0, 8]
+        with pytest.raises(binding.EepError) as ei:
+            ctx.check_layout(wl.T - 32)
+        assert ei.value.code == binding.ERR_STATE
     finally:
         ctx.destroy()
 
