@@ -328,6 +328,31 @@ def test_prefill_fp8_full_size_every_token(oracle):
             assert np.array_equal(out_got, chain), f"combined rows, tokens from {t0}"
             print(f"prefill parity: tokens {t0}..{t0 + chunk - 1} ok", flush=True)
         assert seen.all()                       # the chunks' rows are all N rows of the buffer
+
+        # the same step in the launch configuration the benchmark times: eight steps captured
+        # into one hipGraph and replayed; every buffer must come out as in the eager step that
+        # was just compared with the oracle
+        want = [t.clone() for t in (dev.recv, dev.recv_scale, dev.y, dev.out)]
+        lay_eager = got
+        stream = torch.cuda.Stream()
+        dev.stream = stream
+        ctx.graph_begin(stream)
+        for _ in range(8):
+            dev.step()
+        graph = ctx.graph_end(stream)
+        for replay in range(2):
+            for t in (dev.recv, dev.recv_scale, dev.y, dev.out):
+                t.fill_(0)
+            torch.cuda.synchronize()
+            graph.launch(stream)
+            stream.synchronize()
+            gu.assert_layout_equal(ctx.read_layout(T, stream), lay_eager, T, k)
+            for name, a, b in zip(("payload", "scales", "dequantised", "combined"),
+                                  (dev.recv, dev.recv_scale, dev.y, dev.out), want):
+                assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), \
+                    f"{name} rows differ in graph replay {replay}"
+        assert graph.counters() == dict(instantiations=1, exec_updates=0, launches=2)
+        graph.destroy()
     finally:
         ctx.destroy()
 
