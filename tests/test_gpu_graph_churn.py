@@ -102,12 +102,16 @@ def test_churn_1000_replays_one_instantiation(oracle):
         ctx.destroy()
 
 
-def test_decode_full_size_as_the_benchmark_launches_it(oracle):
+@pytest.mark.parametrize("router", ["uniform", "zipf"])
+def test_decode_full_size_as_the_benchmark_launches_it(oracle, router):
     """The launch configuration the benchmark times: DeepSeek-V3 decode shape at full
     size, identity expert (y aliases the receive buffer), EIGHT steps captured in one
     hipGraph on a side stream, replayed with table patches and eager work in between.
-    Every output row of every step of every replay is compared with the oracle."""
-    wl = synth.decode()
+    Every output row of every step of every replay is compared with the oracle.
+    "zipf": the router of the failed-rank configuration, whose hottest experts are the ones
+    that move to redundant slots when rank 13 fails (the hottest slot takes ~4000 rows)."""
+    wl = synth.decode() if router == "uniform" else synth.decode_failed_zipf()
+    wl.p2l = wl.p2l_preferred                     # start healthy; the failure comes mid-test
     T, k, H, R = wl.T, wl.k, wl.H, wl.R
     failed = (13,)
     dead, live = synth.active_mask(R, failed), synth.active_mask(R)
