@@ -121,6 +121,41 @@ def time_events(stream, fn, reps):
     return e0.elapsed_time(e1) / reps  # ms
 
 
+def streaming_yardsticks(stream, plane_d, plane_c):
+    """What the memory system gives the step's two read:write mixes when nothing is scattered:
+    perfectly sequential kernels (eep_calibration_stream: same loads and stores as pack and
+    combine) that read one plane of plane_d bytes and write eight (dispatch's mix), read eight
+    planes of plane_c bytes and write one (combine's mix), each looped alone and the two
+    alternating as in a step (x -> receive rows -> out), plus a copy of 512 MiB."""
+    import torch
+    from paper_2605_10670_amd import binding
+    pad = 4368 * 16                      # keeps the planes from being a power of two apart
+    stride = max(plane_d, plane_c) + pad
+    size = max(8 * stride, 512 << 20)
+    a = torch.ones(size, dtype=torch.uint8, device="cuda")
+    b = torch.zeros(size, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    d_mix = lambda: binding.calibration_stream(b, a, plane_d, stride, 1, 8, stream)
+    c_mix = lambda: binding.calibration_stream(a, b, plane_c, stride, 8, 1, stream)
+    copy = lambda: binding.calibration_stream(b, a, 512 << 20, 512 << 20, 1, 1, stream)
+
+    def pair():
+        d_mix()
+        c_mix()
+
+    out = {}
+    for name, fn, nbytes in (("copy_512MiB", copy, 2 * (512 << 20)), ("read1_write8", d_mix, 9 * plane_d),
+                             ("read8_write1", c_mix, 9 * plane_c),
+                             ("read1_write8_then_read8_write1", pair, 9 * (plane_d + plane_c))):
+        for _ in range(3):
+            fn()
+        us = time_events(stream, fn, 16) * 1e3
+        out[name] = {"us": us, "bytes": nbytes, "gbs": nbytes / us / 1e3,
+                     "frac_of_hbm_peak": nbytes / us / 1e3 / HBM_PEAK_GBS}
+    del a, b
+    return out
+
+
 def cpu_model():
     try:
         for line in open("/proc/cpuinfo"):
@@ -446,6 +481,8 @@ def main():
                     help="for counter runs: after one whole step, launch only this stage --steps "
                          "times (out of sequence) and print its mean time; nothing else is measured")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--no-yardsticks", action="store_true",
+                    help="skip the sequential streaming kernels with the step's read:write mixes")
     ap.add_argument("--calib", action="store_true",
                     help="first launch 5 plain copy kernels of 512 MiB (k_calibration_copy), the "
                          "yardstick for rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -722,6 +759,10 @@ def main():
     }
     if isolated is not None:
         result["isolated_us"] = isolated
+    if k == 8 and not args.no_yardsticks:
+        # same byte counts as the two data stages, perfectly sequential (no permutation)
+        result["streaming_yardsticks"] = streaming_yardsticks(
+            stream, nbytes["dispatch"] // 9 // 16 * 16, nbytes["combine"] // 9 // 16 * 16)
     if dedup_info is not None:
         result["dedup"] = dedup_info
     if not args.no_cpu:

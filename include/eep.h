@@ -360,6 +360,25 @@ int eep_debug_check_layout(eep_ctx* ctx, int32_t T, int32_t violations_host[4], 
  * hardware HBM counters are scaled by when a profile is turned into bytes. */
 int eep_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream);
 
+/* Measurement helper: a perfectly sequential streaming kernel with the read:write
+ * mix of a stage of the step, as a yardstick for what the memory system gives
+ * that mix when nothing is scattered (paper Sec. 6.2 names dispatch and combine
+ * as the dominant cost; both are pure data movement).  Thread i reads 16-byte
+ * vector i of `reads` source planes and writes vector i of `writes` destination
+ * planes, with the loads and stores that pack and combine use (read-once
+ * non-temporal loads, write-through stores).  (reads, writes) in {1, 8}^2:
+ * (1, 8) is dispatch's mix, (8, 1) combine's, (1, 1) a copy.
+ *   src, dst            device, 16-byte aligned; plane j starts j * plane_stride_bytes
+ *                       in; src holds `reads` planes, dst `writes` planes; must not overlap
+ *   plane_bytes         bytes per plane, a multiple of 16 (0: nothing is launched)
+ *   plane_stride_bytes  >= plane_bytes, a multiple of 16 (a stride that is not a
+ *                       power of two keeps the planes off one another's channels)
+ * Moves exactly reads * plane_bytes in and writes * plane_bytes out.  Asynchronous
+ * on `stream`; EEP_ERR_INVALID_ARG for anything else. */
+int eep_calibration_stream(void* dst, const void* src, int64_t plane_bytes,
+                           int64_t plane_stride_bytes, int32_t reads, int32_t writes,
+                           void* stream);
+
 const char* eep_strerror(int code);
 /* hipError_t of the last failed HIP call made for this context (0 if none). */
 int eep_last_hip_error(eep_ctx* ctx);

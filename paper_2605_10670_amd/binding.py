@@ -94,6 +94,7 @@ def load():
         "eep_read_view": [vp, i32, vp, i64, vp],
         "eep_last_hip_error": [vp],
         "eep_calibration_copy": [vp, vp, i64, vp],
+        "eep_calibration_stream": [vp, vp, i64, i64, i32, i32, vp],
         "eep_host_replica_lists": [i32, i32, i32, i32, vp, vp, vp],
         "eep_host_uncovered_experts": [i32, i32, i32, vp, vp],
         "eep_host_tiling": [i32, i32, vp],
@@ -166,6 +167,13 @@ def calibration_copy(dst, src, nbytes, stream=None):
     """Plain copy kernel of known size (yardstick for HBM counters)."""
     _check(load().eep_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)),
            "eep_calibration_copy")
+
+
+def calibration_stream(dst, src, plane_bytes, plane_stride_bytes, reads, writes, stream=None):
+    """Sequential streaming kernel with a given read:write mix (yardstick for the data kernels)."""
+    _check(load().eep_calibration_stream(_ptr(dst), _ptr(src), plane_bytes, plane_stride_bytes,
+                                         reads, writes, _stream(stream)),
+           "eep_calibration_stream")
 
 
 def host_replica_lists(p2l, E, S, S_prim):

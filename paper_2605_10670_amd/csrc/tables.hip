@@ -48,23 +48,4 @@ hipError_t launch_fill(int32_t* dst, int32_t value, int64_t n, hipStream_t st) {
   return hipGetLastError();
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__global__ __launch_bounds__(256) void k_calibration_copy(const u32x4* __restrict__ src,
-                                                          u32x4* __restrict__ dst, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) dst[i] = src[i];
-}
-
 }  // namespace eep
-
-extern "C" int eep_calibration_copy(void* dst, const void* src, int64_t bytes, void* stream) {
-  if (!dst || !src || bytes < 0 || bytes % 16 != 0 || ((uintptr_t)dst & 15) ||
-      ((uintptr_t)src & 15) || bytes / 16 / 256 >= ((int64_t)1 << 31))
-    return EEP_ERR_INVALID_ARG;
-  if (bytes == 0) return EEP_OK;
-  int64_t n = bytes / 16;
-  hipLaunchKernelGGL(eep::k_calibration_copy, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                     (hipStream_t)stream, (const eep::u32x4*)src, (eep::u32x4*)dst, n);
-  return hipGetLastError() == hipSuccess ? EEP_OK : EEP_ERR_HIP;
-}
