@@ -69,6 +69,10 @@ def load():
         except Exception as exc:
             raise RuntimeError(f"{LIB_PATH} is missing and could not be built with hipcc ({exc}); "
                                "there is no fallback path") from exc
+    # torch brings a HIP runtime of its own.  It has to be in the process before this library
+    # binds its hip* symbols, so that both use the same one: two runtimes in one process do
+    # not share a device context, and tensors of one are not valid arguments for the other.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     sig = {

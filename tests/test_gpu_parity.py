@@ -769,3 +769,23 @@ def test_small_batches_around_the_single_workgroup_limit(oracle, policy, R, T, k
     got, _ = run_and_compare(oracle, wl, policy=policy, strict=False)
     for r in failed:
         assert got["rank_count"][r] == 0
+
+
+def test_smoke_in_a_fresh_process_that_loads_the_library_before_torch():
+    """build() ends with binding.load(); a process that goes on to smoke() has then loaded the
+    library before it imports torch.  The binding brings torch (and its HIP runtime) in first
+    by itself, so the order in the caller's code does not matter."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2605_10670_amd import binding\n"
+            "assert 'torch' not in sys.modules\n"
+            "binding.load()\n"
+            "import __graft_entry__ as g\n"
+            "g.smoke()\n" % root)
+    done = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300,
+                          cwd=root)
+    assert done.returncode == 0, done.stdout[-2000:] + done.stderr[-2000:]
+    assert "smoke ok" in done.stdout
