@@ -161,6 +161,7 @@ int eep_apply_repair(eep_ctx* c, void* weights, const void* backup, int64_t slot
 
 int eep_read_repair_outcome(eep_ctx* c, int32_t* outcome_host) {
   if (!c || !outcome_host) return EEP_ERR_INVALID_ARG;
+  c = c->tables;  // the repair ran on the tables' owner, whichever context was named
   hipError_t e = hipDeviceSynchronize();
   if (e == hipSuccess)
     e = hipMemcpy(outcome_host, c->mv_outcome, sizeof(int32_t) * (size_t)c->P, hipMemcpyDeviceToHost);

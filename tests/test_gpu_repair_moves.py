@@ -77,6 +77,30 @@ def test_fig5_repair_moves(pinned):
         ctx.destroy()
 
 
+def test_repair_named_through_a_staging_context():
+    """A staging context shares its owner's placement tables: a repair applied through it
+    acts on those, and its outcome can be read through either context."""
+    meta, panels = parse_fig5()
+    S, S_prim, E, R = meta["slots_per_rank"], meta["primary_slots"], meta["experts"], 4
+    before = _panel_placement(panels[0], R, S)
+    active = np.asarray(panels[1]["active"], np.int32)
+    slot_bytes = 65536 + 32
+    weights, backup = _store(np.random.default_rng(6), before, E, slot_bytes)
+    ctx = _context(R, S, S_prim, E, strict=True)
+    stg = ctx.staging()
+    try:
+        ctx.update_placement(before)
+        plan = binding.plan_repair(before, active, R, S, S_prim, E)
+        got_w, got_o = _run(stg, weights, backup, plan, slot_bytes, pinned=False)
+        want_w, want_o = _expect(weights, backup, plan, np.ones(R, np.int32), S)
+        assert np.array_equal(got_o, want_o) and np.array_equal(got_w, want_w)
+        assert np.array_equal(ctx.read_repair_outcome(), want_o)
+        assert ctx.read("phys_to_logical", R * S).tolist() == plan["p2l"].tolist()
+    finally:
+        stg.destroy()
+        ctx.destroy()
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_random_repairs_match_oracle(seed):
     rng = np.random.default_rng(300 + seed)
