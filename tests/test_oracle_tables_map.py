@@ -174,3 +174,50 @@ def test_uncovered_and_masked_are_counted(oracle):
     assert res["n_uncovered"] == int((w.topk_idx == lost).sum()) > 0
     assert res["N"] + res["n_uncovered"] + res["n_masked"] == w.T * w.k
     assert (res["slot_of"][w.topk_idx == lost] == -1).all()
+
+
+def test_spread_balances_and_depends_only_on_token_and_live_set(oracle):
+    """The paper names no replica-selection rule, so the expected slots of SPREAD cannot come
+    from it.  What any sensible spreading rule must satisfy is pinned instead, without
+    restating the oracle's formula: consecutive tokens that want one expert are dealt over
+    its live replicas evenly (every window of n tokens touches all n live replicas, so the
+    per-replica counts differ by at most one), the choice does not depend on the pair's
+    position j, on the token's other experts, or on replicas that are not live."""
+    R, S, S_prim, E, T = 6, 3, 2, 8, 60
+    # expert 6: primary on rank 2 (its second primary slot), redundant copies on ranks 0, 3 and 4
+    p2l = np.full(R * S, -1, np.int32)
+    for r in range(R):
+        p2l[r * S + 0] = r                     # experts 0..5 primary on their rank
+    p2l[2 * S + 1] = 6
+    for r in (0, 3, 4):
+        p2l[r * S + 2] = 6                     # three redundant copies of expert 6
+    p2l[5 * S + 1] = 7
+    off, lst = oracle.tables(p2l, E, S, S_prim)
+    rng = np.random.default_rng(11)
+    for mask in ([1] * R, [1, 1, 0, 1, 1, 1], [0, 1, 1, 1, 0, 1], [0, 1, 0, 1, 0, 1]):
+        active = np.array(mask, np.int32)
+        live = [p for p in range(R * S) if p2l[p] == 6 and mask[p // S]]
+        n = len(live)
+        # every token wants expert 6, at a random position j among two other experts
+        k = 3
+        idx = np.empty((T, k), np.int32)
+        pos = rng.integers(0, k, size=T)
+        for t in range(T):
+            others = rng.choice([0, 1, 3, 5, 7], size=k - 1, replace=False)
+            idx[t] = np.insert(others, pos[t], 6)
+        slot_of, _, _ = oracle.map_pairs(idx, off, lst, active, E, S, 0)
+        chosen = np.array([slot_of[t, pos[t]] for t in range(T)])
+        assert set(chosen.tolist()) <= set(live)
+        for t0 in range(T - n + 1):                                  # every window is a full deal
+            assert set(chosen[t0:t0 + n].tolist()) == set(live), (mask, t0)
+        counts = np.bincount(chosen, minlength=R * S)[live]
+        assert counts.max() - counts.min() <= 1
+        # the same tokens with expert 6 alone in the token, at j = 0: same choices
+        alone, _, _ = oracle.map_pairs(np.full((T, 1), 6, np.int32), off, lst, active, E, S, 0)
+        assert np.array_equal(alone[:, 0], chosen)
+        # emptying the slots of dead ranks changes nothing
+        pruned = p2l.copy()
+        pruned[[p for p in range(R * S) if not mask[p // S]]] = -1
+        off2, lst2 = oracle.tables(pruned, E, S, S_prim)
+        again, _, _ = oracle.map_pairs(idx, off2, lst2, active, E, S, 0)
+        assert np.array_equal(np.array([again[t, pos[t]] for t in range(T)]), chosen)
