@@ -31,6 +31,27 @@ def test_hazards_are_refused(events):
         pl.validate(events)
 
 
+def test_placement_updates_only_when_no_step_is_in_flight():
+    """Sec. 3.1: repair happens between forward passes.  With the pipeline drained a placement
+    update is accepted and binds to the steps dispatched after it; with one or both staging
+    sets holding a dispatched step it is refused."""
+    seen = []
+    drained = [(pl.D, 0), (pl.D, 1), (pl.C, 0), (pl.C, 1), (pl.UPDATE_PLACEMENT, "B"),
+               (pl.D, 2), (pl.C, 2)]
+    pl.validate(drained)
+    pl.validate([(pl.UPDATE_PLACEMENT, "B")])                          # an idle pipeline too
+    got = pl.run(drained, lambda i, p2l, act: seen.append((i, p2l, act)) or (i, p2l), "A", "m")
+    assert seen == [(0, "A", "m"), (1, "A", "m"), (2, "B", "m")]
+    assert got == {0: (0, "A"), 1: (1, "A"), 2: (2, "B")}
+    for busy in ([(pl.D, 0), (pl.UPDATE_PLACEMENT, "B"), (pl.C, 0)],                    # one set
+                 [(pl.D, 0), (pl.D, 1), (pl.UPDATE_PLACEMENT, "B"), (pl.C, 0), (pl.C, 1)],  # both
+                 [(pl.D, 0), (pl.D, 1), (pl.C, 0), (pl.UPDATE_PLACEMENT, "B"), (pl.C, 1)]):
+        with pytest.raises(pl.ScheduleError):
+            pl.validate(busy)
+    with pytest.raises(pl.ScheduleError):
+        pl.validate([("rewind", 0)])                                    # unknown events too
+
+
 def test_membership_updates_are_allowed_mid_flight_and_bind_at_dispatch(oracle):
     """The scalar stand-in gives out[t] = (sum over covered j of w_j s[e_j]) x[t]; which pairs
     are covered depends only on the mask in force at the step's dispatch.  Placement without

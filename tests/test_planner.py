@@ -199,6 +199,24 @@ def test_transition_library_matches_plain_statement():
         for key in ("p2l", "kind", "src_slot"):
             assert np.asarray(got[key]).tolist() == list(want[key]), (trial, key)
         assert (got["local"], got["peer"], got["dram"]) == (want["local"], want["peer"], want["dram"])
+        assert got["unplaced"] == want["unplaced"] == 0           # a transition places what it is told
+
+
+def test_codes_are_the_ones_the_header_declares():
+    """The plain statement's source kinds and outcome codes are compared with the library's by
+    value in the GPU tests, so they must be the header's values (and distinct)."""
+    import os
+    import re
+    text = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                             "include", "eep.h")).read()
+    enum = {m.group(1): int(m.group(2)) for m in re.finditer(r"\b(EEP_[A-Z_]+)\s*=\s*(-?\d+)", text)}
+    assert (ref.NONE, ref.LOCAL, ref.PEER, ref.DRAM) == (
+        enum["EEP_SRC_NONE"], enum["EEP_SRC_LOCAL"], enum["EEP_SRC_PEER"], enum["EEP_SRC_DRAM"])
+    assert (ref.UNTOUCHED, ref.FROM_PEER, ref.FROM_DRAM, ref.FROM_DRAM_FALLBACK) == (
+        enum["EEP_REPAIR_UNTOUCHED"], enum["EEP_REPAIR_FROM_PEER"], enum["EEP_REPAIR_FROM_DRAM"],
+        enum["EEP_REPAIR_FROM_DRAM_FALLBACK"])
+    assert len({ref.NONE, ref.LOCAL, ref.PEER, ref.DRAM}) == 4
+    assert len({ref.UNTOUCHED, ref.FROM_PEER, ref.FROM_DRAM, ref.FROM_DRAM_FALLBACK}) == 4
 
 
 def test_transition_argument_errors():
