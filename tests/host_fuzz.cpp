@@ -23,6 +23,22 @@ void eeo_combine_chain32(int T, int k, int H, int y_dtype, const void* y, const 
                          const int32_t* row_of, float* out);
 int64_t eeo_detect_round(int T, int k, int R, int S, const int32_t* slot_of, const int32_t* arrived,
                          int32_t* active, int32_t* report, int32_t* row_of);
+void eeo_combine(int T, int k, int H, int y_dtype, const void* y, const float* w, const int32_t* row_of,
+                 double* out);
+void eeo_dedup_layout(int T, int k, int R, int S, const int32_t* slot_of, const int32_t* row_of,
+                      int32_t* dedup_count, int32_t* dedup_offset, int32_t* dedup_row, int32_t* lead,
+                      int32_t* expand_of, int32_t* seen);
+void eeo_pack_dedup(int T, int k, int64_t row_bytes, const uint8_t* x, const int32_t* dedup_row,
+                    const int32_t* lead, uint8_t* recv_d);
+void eeo_expand(int N, int64_t row_bytes, const uint8_t* recv_d, const int32_t* expand_of, uint8_t* recv);
+void eeo_stub_scale(int N, int H, int P, int dtype, const void* recv, const int32_t* offset,
+                    const int32_t* p2l, const float* expert_scale, void* y);
+void eeo_stub_dequant(int N, int H, int group, const uint8_t* q, const float* scale, uint16_t* y);
+void eeo_quantize_e4m3(int T, int H, int group, const uint16_t* x, uint8_t* q, float* scale);
+void eeo_bf16_to_f32_array(int64_t n, const uint16_t* in, float* out);
+void eeo_f32_to_bf16_array(int64_t n, const float* in, uint16_t* out);
+void eeo_f32_to_e4m3_array(int64_t n, const float* in, uint8_t* out);
+void eeo_e4m3_to_f32_array(int64_t n, const uint8_t* in, float* out);
 }
 
 #define REQUIRE(cond)                                                   \
@@ -121,6 +137,38 @@ int main(int argc, char** argv) {
       }
       REQUIRE(gone == expect);
       eeo_combine_chain32(T, k, H, 0, recv.data(), w.data(), row2.data(), out.data());
+      std::vector<double> out64((size_t)T * H);
+      eeo_combine(T, k, H, 0, recv.data(), w.data(), row2.data(), out64.data());
+      for (size_t i = 0; i < out.size(); ++i) REQUIRE((double)out[i] == out64[i]);  // small integers: exact
+
+      // the remaining oracle functions, every buffer allocated at exactly the size the
+      // function's contract names (so that the sanitizer sees any step past an end)
+      std::vector<int32_t> dcount(R), doff(R + 1), drow((size_t)T * k), lead((size_t)T * k),
+          expand((size_t)T * k), seen_r(R);
+      eeo_dedup_layout(T, k, R, S, slot.data(), row.data(), dcount.data(), doff.data(), drow.data(),
+                       lead.data(), expand.data(), seen_r.data());
+      const int Nd = doff[R];
+      REQUIRE(Nd <= N);
+      std::vector<float> recv_d((size_t)Nd * H), recv_x((size_t)N * H);
+      eeo_pack_dedup(T, k, H * 4, (const uint8_t*)x.data(), drow.data(), lead.data(), (uint8_t*)recv_d.data());
+      eeo_expand(N, H * 4, (const uint8_t*)recv_d.data(), expand.data(), (uint8_t*)recv_x.data());
+      REQUIRE(N == 0 || std::memcmp(recv_x.data(), recv.data(), (size_t)N * H * 4) == 0);  // two stages = pack
+      std::vector<float> es(E), y32((size_t)N * H);
+      for (int e = 0; e < E; ++e) es[e] = 1.0f + e;
+      eeo_stub_scale(N, H, P, 0, recv_x.data(), offset.data(), nw.data(), es.data(), y32.data());
+      for (int r = 0; r < N; ++r) REQUIRE(y32[(size_t)r * H] == es[idx[srcof[r]]] * recv_x[(size_t)r * H]);
+      const int group = 2, G = H / group;
+      std::vector<uint16_t> xb((size_t)T * H), yb((size_t)T * H);
+      eeo_f32_to_bf16_array((int64_t)T * H, x.data(), xb.data());
+      std::vector<uint8_t> q((size_t)T * H);
+      std::vector<float> sc((size_t)T * G), back((size_t)T * H);
+      eeo_quantize_e4m3(T, H, group, xb.data(), q.data(), sc.data());
+      eeo_stub_dequant(T, H, group, q.data(), sc.data(), yb.data());
+      eeo_bf16_to_f32_array((int64_t)T * H, yb.data(), back.data());
+      for (size_t i = 0; i < back.size(); ++i) REQUIRE(back[i] - x[i] <= 0.5f && x[i] - back[i] <= 0.5f);
+      eeo_f32_to_e4m3_array((int64_t)T * H, x.data(), q.data());
+      eeo_e4m3_to_f32_array((int64_t)T * H, q.data(), back.data());
+      for (size_t i = 0; i < back.size(); ++i) REQUIRE(back[i] == x[i]);  // |x| <= 8 integers are e4m3 values
     }
   }
   std::printf("ok %d\n", iterations);
