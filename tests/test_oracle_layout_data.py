@@ -85,6 +85,15 @@ def test_bf16_and_e4m3_formats_match_torch(oracle):
     want16 = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
     assert np.array_equal(oracle.f32_to_bf16(x), want16)
     assert np.array_equal(synth.f32_to_bf16_bits(x), want16)
+    # NaN stays NaN with its sign (IEEE 754 conversion; which payload bits survive is not fixed,
+    # only that the result is a quiet NaN), whatever the payload: also one that lives only in
+    # the 16 bits that the narrower format drops
+    nan_bits = np.array([0x7FC00000, 0xFFC00000, 0x7F800001, 0xFF800001, 0x7F80FFFF, 0x7FFFFFFF,
+                         0xFFFFFFFF, 0x7FA00000], np.uint32)
+    got_nan = oracle.f32_to_bf16(nan_bits.view(np.float32)).astype(np.uint32)
+    assert ((got_nan & 0x7F80) == 0x7F80).all() and ((got_nan & 0x007F) != 0).all()
+    assert ((got_nan & 0x0040) != 0).all()                                   # quiet
+    assert np.array_equal(got_nan >> 15, nan_bits >> 31)                     # sign kept
     codes = np.arange(256, dtype=np.uint8)
     want8 = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
     got8 = oracle.e4m3_to_f32(codes)
