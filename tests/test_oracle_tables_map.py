@@ -95,6 +95,9 @@ def test_tables_reject_out_of_range(oracle):
         oracle.tables(np.array([0, 7], np.int32), 4, 2, 1)
     with pytest.raises(ValueError):
         oracle.tables(np.array([0, -2], np.int32), 4, 2, 1)
+    with pytest.raises(ValueError):
+        oracle.tables(np.array([0, 4], np.int32), 4, 2, 1)      # E itself is the first invalid id
+    oracle.tables(np.array([3, -1], np.int32), 4, 2, 1)         # E - 1 and "empty" are the last valid
 
 
 def _brute_slot(e, t, p2l, active, S, S_prim, E, policy, earlier):
