@@ -230,7 +230,8 @@ SRC_NONE, SRC_LOCAL, SRC_PEER, SRC_DRAM = -1, 0, 1, 2
 
 def plan_repair(cur_p2l, active, R, S, S_prim, E, load=None):
     """Repaired placement + source of every slot's weights (host only).
-    Returns dict(p2l, kind, src_slot, local, peer, dram, unplaced)."""
+    Returns dict(p2l, kind, src_slot, local, peer, dram, unplaced, status); status is the
+    library's return code: OK, or ERR_COVERAGE when experts stayed unplaced."""
     cur = np.ascontiguousarray(cur_p2l, np.int32)
     act = np.ascontiguousarray(active, np.int32)
     if cur.size != R * S or act.size != R:
@@ -244,7 +245,7 @@ def plan_repair(cur_p2l, active, R, S, S_prim, E, load=None):
     if rc not in (OK, ERR_COVERAGE):
         _check(rc, "eep_plan_repair")
     return dict(p2l=new, kind=kind, src_slot=src, local=int(summary[0]), peer=int(summary[1]),
-                dram=int(summary[2]), unplaced=int(summary[3]))
+                dram=int(summary[2]), unplaced=int(summary[3]), status=rc)
 
 
 def workspace_bytes(*, num_ranks, slots_per_rank, primary_slots, num_logical, max_tokens, topk, hidden,

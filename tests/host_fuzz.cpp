@@ -66,6 +66,7 @@ int main(int argc, char** argv) {
     int rc = eep_plan_repair(R, S, Sp, E, cur.data(), act.data(), it % 2 ? load.data() : nullptr,
                              nw.data(), kind.data(), src.data(), sum);
     REQUIRE(rc == EEP_OK || rc == EEP_ERR_COVERAGE);
+    REQUIRE((rc == EEP_ERR_COVERAGE) == (sum[3] > 0));
     for (int p = 0; p < P; ++p) {
       REQUIRE(nw[p] >= -1 && nw[p] < E);
       REQUIRE(kind[p] >= EEP_SRC_NONE && kind[p] <= EEP_SRC_DRAM);

@@ -74,3 +74,72 @@ def test_tiling_partitions_every_source_rank(R):
         assert g["tiles_per_rank"] == -(-per_rank // 128)
     with pytest.raises(binding.EepError):
         binding.host_tiling(R + 1 if R > 1 else -1, R)
+
+
+def test_every_argument_check_of_the_host_entry_points():
+    """One invalid argument at a time (each size, each pointer, the first id on either side of
+    the valid range) must be refused with EEP_ERR_INVALID_ARG; the unchanged call succeeds."""
+    import ctypes
+    lib = binding.load()
+    BAD = binding.ERR_INVALID_ARG
+    R, S, S_prim, E = 3, 2, 1, 4
+    P = R * S
+    I = lambda *v: np.array(v, np.int32)
+    cur, tgt = I(0, 1, 2, 3, -1, 0), I(1, 0, 2, 3, 3, -1)
+    act, wr = I(1, 0, 1), I(1, 1, 1)
+    new, kind, src = (np.zeros(P, np.int32) for _ in range(3))
+    summ = np.zeros(4, np.int32)
+    load = np.ones(E, np.float32)
+    p = lambda a: None if a is None else a.ctypes.data
+
+    def repair(R=R, S=S, S_prim=S_prim, E=E, cur=cur, act=act, load=load, new=new, kind=kind,
+               src=src, summ=summ):
+        return lib.eep_plan_repair(R, S, S_prim, E, p(cur), p(act), p(load), p(new), p(kind), p(src),
+                                   p(summ))
+
+    def transition(R=R, S=S, S_prim=S_prim, E=E, cur=cur, tgt=tgt, act=act, wr=wr, new=new,
+                   kind=kind, src=src, summ=summ):
+        return lib.eep_plan_transition(R, S, S_prim, E, p(cur), p(tgt), p(act), p(wr), p(new),
+                                       p(kind), p(src), p(summ))
+
+    off, lst = np.zeros(E + 1, np.int32), np.zeros(P, np.int32)
+
+    def lists(P=P, E=E, S=S, S_prim=S_prim, p2l=cur, off=off, lst=lst):
+        return lib.eep_host_replica_lists(P, E, S, S_prim, p(p2l), p(off), p(lst))
+
+    def uncovered(P=P, E=E, S=S, p2l=cur, act=act):
+        return lib.eep_host_uncovered_experts(P, E, S, p(p2l), p(act))
+
+    out4 = np.zeros(4, np.int32)
+
+    def tiling(T=12, R=R, out=out4):
+        return lib.eep_host_tiling(T, R, p(out))
+
+    assert repair() == binding.OK and repair(load=None) == binding.OK
+    assert transition() == binding.OK and lists() == binding.OK and tiling() == binding.OK
+    assert uncovered() == 2 and tiling(T=0) == binding.OK       # experts 2 and 3 live on the dead rank only
+    hi, lo = cur.copy(), cur.copy()
+    hi[2], lo[3] = E, -2
+    sizes = [dict(R=0), dict(S=0), dict(S_prim=-1), dict(S_prim=S + 1), dict(E=0)]
+    for kw in sizes + [dict(cur=None), dict(act=None), dict(new=None), dict(kind=None),
+                       dict(src=None), dict(summ=None), dict(cur=hi), dict(cur=lo),
+                       dict(load=np.array([1, -1, 1, 1], np.float32)),
+                       dict(load=np.array([1, np.nan, 1, 1], np.float32))]:
+        assert repair(**kw) == BAD, kw
+    for kw in sizes + [dict(cur=None), dict(tgt=None), dict(act=None), dict(wr=None),
+                       dict(new=None), dict(kind=None), dict(src=None), dict(summ=None),
+                       dict(cur=hi), dict(cur=lo), dict(tgt=hi), dict(tgt=lo)]:
+        assert transition(**kw) == BAD, kw
+    for kw in [dict(P=0), dict(E=0), dict(S=0), dict(S_prim=-1), dict(S_prim=S + 1), dict(P=P - 1),
+               dict(p2l=None), dict(off=None), dict(lst=None), dict(p2l=hi), dict(p2l=lo)]:
+        assert lists(**kw) == BAD, kw
+    for kw in [dict(P=0), dict(E=0), dict(S=0), dict(P=P - 1), dict(p2l=None), dict(act=None),
+               dict(p2l=hi), dict(p2l=lo)]:
+        assert uncovered(**kw) == BAD, kw
+    for kw in [dict(T=-3), dict(R=0), dict(T=13), dict(out=None)]:
+        assert tiling(**kw) == BAD, kw
+    # the ids on the valid side of each boundary are accepted
+    edge = cur.copy()
+    edge[2], edge[3] = E - 1, -1
+    assert repair(cur=edge) in (binding.OK, binding.ERR_COVERAGE) and transition(cur=edge, tgt=edge) == binding.OK
+    assert lists(p2l=edge) == binding.OK and uncovered(p2l=edge) >= 0

@@ -131,6 +131,8 @@ def test_library_matches_plain_statement_and_invariants(seed):
         live_slots = int(active.sum()) * S
         assert a["unplaced"] == max(0, E - live_slots)
         assert binding.host_uncovered_experts(a["p2l"], active, E, S) == a["unplaced"]
+        # the library's return code says the same: coverage error exactly when experts are left over
+        assert a["status"] == (binding.ERR_COVERAGE if a["unplaced"] else binding.OK)
 
 
 def test_failure_scales_shift_from_peer_to_dram():
@@ -172,6 +174,7 @@ def test_tiny_infeasible_case_reports_one_uncovered_expert():
     wl = synth.tiny("b")
     out = binding.plan_repair(wl.p2l_preferred, wl.active, wl.R, wl.S, wl.S_prim, wl.E)
     assert out["unplaced"] == 1                       # 15 live slots < 16 experts
+    assert out["status"] == binding.ERR_COVERAGE
 
 
 def test_bad_arguments():
