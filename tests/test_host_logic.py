@@ -138,6 +138,12 @@ def test_every_argument_check_of_the_host_entry_points():
         assert uncovered(**kw) == BAD, kw
     for kw in [dict(T=-3), dict(R=0), dict(T=13), dict(out=None)]:
         assert tiling(**kw) == BAD, kw
+    # sizes that are wrong although every entry would pass: no experts with all slots empty,
+    # no slots per rank with no primary slots
+    empty = np.full(P, -1, np.int32)
+    assert lists(E=0, p2l=empty) == BAD and uncovered(E=0, p2l=empty) == BAD
+    assert repair(E=0, cur=empty, load=None) == BAD and transition(E=0, cur=empty, tgt=empty) == BAD
+    assert lists(S=0, S_prim=0) == BAD and repair(S=0, S_prim=0) == BAD
     # the ids on the valid side of each boundary are accepted
     edge = cur.copy()
     edge[2], edge[3] = E - 1, -1
