@@ -26,6 +26,13 @@
  *     table updates rewrite contents only (Fig. 4, Fig. 8), which is what lets
  *     a captured hipGraph keep replaying across failure and rejoin.
  *   - Layouts are dense row-major; indices are int32.
+ *   - Threads: calls on DIFFERENT contexts that share no membership instance
+ *     may run concurrently.  Calls that name one context, or contexts of one
+ *     instance (eep_create_attached, eep_create_staging), keep host-side state
+ *     (shadow copies of the tables, the last laid-out T) without locks: the
+ *     caller serialises them.  On the device, work of one context is ordered
+ *     by the streams the caller passes; two steps of one context queued on two
+ *     streams without an event between them race on its layout arrays.
  *
  * Notation: T tokens, k = top-k, H hidden elements, E logical experts,
  * R ranks, S slots per rank (S_prim primary + S_red redundant), P = R*S
